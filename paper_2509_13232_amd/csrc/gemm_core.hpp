@@ -1,0 +1,171 @@
+// bf16 MFMA contraction core for gfx950 (CDNA4, 64-wide wavefronts).
+//
+// Computes a BM x BN tile of  D[m][n] = sum_k A[m][k] * B[n][k]  where both
+// operands are row-major with the contraction index contiguous.  All three
+// contractions of the loss (logits = W h, dHidden = dZ W, dW = dZ^T X) are
+// brought to this form by the callers, so there is one main loop to tune.
+//
+// Data path per K step of 64 elements (128 bytes per operand row):
+//   HBM/L2 --global_load_lds_dwordx4--> LDS (two stages)  --ds_read_b128-->
+//   VGPR fragments --v_mfma_f32_32x32x16_bf16--> fp32 accumulators.
+// Global loads go straight to LDS without passing through registers.  A tile
+// row is 8 chunks of 16 bytes; chunk c of row r is stored at chunk position
+// c ^ swz(r), which makes both the 64 lanes x 16 B fragment reads and the
+// linear DMA writes free of bank conflicts.  The swizzle is applied on the
+// global side (each lane fetches the chunk that belongs at its LDS slot),
+// because the DMA writes lane i at base + 16*i.
+//
+// Accumulator layout of one 32x32 block (v_mfma_f32_32x32x16_bf16): lane l
+// holds column n = l % 32 and, in register r, row m = 8*(r/4) + 4*(l/32) + r%4.
+// Callers put the index they reduce over or scale by per row of the tile
+// (vocabulary entries) on m and the index with per-lane constants (tokens) on n.
+#pragma once
+
+#include "common.hpp"
+
+namespace spo {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+constexpr int kBK = 64;  // contraction elements per stage
+
+// chunk swizzle of a tile row; a bijection on 0..7 both over rows 0..7 and over
+// the rows of equal parity in 0..15
+__device__ __forceinline__ int swz(int row) {
+    return ((row >> 1) & 3) | (((row ^ (row >> 3)) & 1) << 2);
+}
+
+template <int BM_, int BN_, int WGM_, int WGN_>
+struct Tile {
+    static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_;
+    static constexpr int NWAVE = WGM * WGN, NT = NWAVE * kWave;
+    static constexpr int WM = BM / WGM, WN = BN / WGN;     // wave tile
+    static constexpr int FM = WM / 32, FN = WN / 32;       // 32x32 blocks per wave
+    static constexpr int A_BYTES = BM * kBK * 2, B_BYTES = BN * kBK * 2;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
+    static constexpr int A_LOADS = BM * 8 / NT, B_LOADS = BN * 8 / NT;
+    static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile rows must split evenly over the threads");
+    static_assert((NT / 8) % 16 == 0, "swizzle must be the same for every load of a thread");
+    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile is made of 32x32 blocks");
+
+    typedef f32x16_t Acc[FM][FN];
+
+    __device__ static __forceinline__ int wave_id() {
+        return __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x) / kWave);
+    }
+    __device__ static __forceinline__ int wave_m0() { return (wave_id() % WGM) * WM; }
+    __device__ static __forceinline__ int wave_n0() { return (wave_id() / WGM) * WN; }
+    // tile row of accumulator register r of block fm (add the block's tile origin)
+    __device__ static __forceinline__ int acc_row(int fm, int r) {
+        return wave_m0() + fm * 32 + 8 * (r >> 2) + 4 * ((threadIdx.x & 63) >> 5) + (r & 3);
+    }
+    // tile column of block fn
+    __device__ static __forceinline__ int acc_col(int fn) {
+        return wave_n0() + fn * 32 + (threadIdx.x & 31);
+    }
+
+    // acc += A[m0.., :K] * B[n0.., :K]^T.  Rows beyond M / N are read from the last
+    // valid row (the caller masks them).  K = 64 * KT.  lds: LDS_BYTES bytes,
+    // 16-byte aligned.  All threads of the block must call this together.
+    __device__ static __forceinline__ void mainloop(const char *__restrict__ A, int64_t lda_bytes, int64_t m0, int64_t M,
+                                                    const char *__restrict__ B, int64_t ldb_bytes, int64_t n0, int64_t N,
+                                                    int KT, char *lds, Acc &acc) {
+        const int tid = threadIdx.x, lane = tid & 63, wave = wave_id();
+        // ---- DMA addressing: slot q = i*NT + tid of a tile <-> (row q/8, position q%8)
+        const int ld_row = tid >> 3;
+        const int ld_chunk = (tid & 7) ^ swz(ld_row & 15);
+        // 32-bit byte offsets from the tile's first row (a tile spans < 4 GiB)
+        const char *a_tile = A + m0 * lda_bytes, *b_tile = B + n0 * ldb_bytes;
+        uint32_t oa[A_LOADS], ob[B_LOADS];
+#pragma unroll
+        for (int i = 0; i < A_LOADS; ++i) {
+            int64_t r = i * (NT / 8) + ld_row;
+            r = m0 + r < M ? r : M - 1 - m0;
+            oa[i] = static_cast<uint32_t>(r * lda_bytes + ld_chunk * 16);
+        }
+#pragma unroll
+        for (int i = 0; i < B_LOADS; ++i) {
+            int64_t r = i * (NT / 8) + ld_row;
+            r = n0 + r < N ? r : N - 1 - n0;
+            ob[i] = static_cast<uint32_t>(r * ldb_bytes + ld_chunk * 16);
+        }
+        auto issue = [&](int stage, int64_t koff) {
+            char *la = lds + stage * STAGE_BYTES + wave * (kWave * 16);
+            char *lb = la + A_BYTES;
+            const char *ak = a_tile + koff, *bk = b_tile + koff;
+#pragma unroll
+            for (int i = 0; i < A_LOADS; ++i)
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void *)(ak + oa[i]),
+                    (__attribute__((address_space(3))) void *)(la + i * (NT * 16)), 16, 0, 0);
+#pragma unroll
+            for (int i = 0; i < B_LOADS; ++i)
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void *)(bk + ob[i]),
+                    (__attribute__((address_space(3))) void *)(lb + i * (NT * 16)), 16, 0, 0);
+        };
+        // ---- fragment addressing: lane reads row (l%32) of a 32-row block, chunk 2*kk + l/32
+        const int fr_sw = swz(lane & 15);
+        int fr_off[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) fr_off[kk] = (lane & 31) * 128 + (((2 * kk + (lane >> 5)) ^ fr_sw) * 16);
+        const int a_base = wave_m0() * 128, b_base = A_BYTES + wave_n0() * 128;
+
+        __syncthreads();  // every wave is done with the previous contents of lds
+        issue(0, 0);
+        for (int kt = 0; kt < KT; ++kt) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // my part of stage kt has landed
+            __syncthreads();                                  // ... and everyone else's
+            const char *st = lds + (kt & 1) * STAGE_BYTES;
+            bf16x8_t af[FM][4], bf[FN][4];
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+                for (int fm = 0; fm < FM; ++fm)
+                    af[fm][kk] = *reinterpret_cast<const bf16x8_t *>(st + a_base + fm * (32 * 128) + fr_off[kk]);
+#pragma unroll
+                for (int fn = 0; fn < FN; ++fn)
+                    bf[fn][kk] = *reinterpret_cast<const bf16x8_t *>(st + b_base + fn * (32 * 128) + fr_off[kk]);
+            }
+            if (kt + 1 < KT) issue((kt + 1) & 1, static_cast<int64_t>(kt + 1) * (kBK * 2));
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+                for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+                    for (int fn = 0; fn < FN; ++fn)
+                        acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[fm][kk], bf[fn][kk], acc[fm][fn], 0, 0, 0);
+        }
+    }
+
+    __device__ static __forceinline__ void zero(Acc &acc) {
+#pragma unroll
+        for (int fm = 0; fm < FM; ++fm)
+#pragma unroll
+            for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[fm][fn][r] = 0.0f;
+    }
+};
+
+// Maps a linear workgroup id to a tile of an nM x nN tile grid so that the 32
+// workgroups that run together on one XCD (ids equal mod 8 are dispatched to the
+// same XCD and share its L2) form a 4 x 8 patch: 12 operand panels feed 32 tiles.
+// Patches are walked along M first.  Returns false for ids beyond the grid.
+struct TileOrder {
+    int64_t nM, nN, pM, pN;  // tiles and patches per dimension
+    __host__ __device__ TileOrder(int64_t nm, int64_t nn) : nM(nm), nN(nn), pM((nm + 3) / 4), pN((nn + 7) / 8) {}
+    __host__ __device__ int64_t blocks() const { return (pM * pN + 7) / 8 * 8 * 32; }
+    __device__ bool tile(int64_t bid, int64_t &tm, int64_t &tn) const {
+        const int64_t xcd = bid & 7, q = bid >> 3;
+        const int64_t patch = (q >> 5) * 8 + xcd, w = q & 31;
+        if (patch >= pM * pN) return false;
+        tm = (patch % pM) * 4 + (w >> 3);
+        tn = (patch / pM) * 8 + (w & 7);
+        return tm < nM && tn < nN;
+    }
+};
+
+}  // namespace spo

@@ -1,0 +1,518 @@
+// Fused LM-head + clipped policy-gradient loss, forward and backward, on bf16
+// MFMA (Method, PPO-Clip objective over the full vocabulary).  The [T x V] logits
+// never exist in memory:
+//   forward   sweeps vocabulary tiles, keeping a running (max, sum-exp) per token
+//             in registers and catching the sampled token's logit on the way;
+//   backward  recomputes the logits tile by tile, turns them into bf16 logit
+//             gradients dZ for one chunk of tokens at a time, and contracts that
+//             chunk twice (dHidden = dZ W, dW += dZ^T X).
+// All contractions run through the one main loop of gemm_core.hpp in the form
+// D[m][n] = sum_k A[m][k] B[n][k]; small transposition kernels provide the
+// operands whose contraction index is not contiguous in the caller's layout.
+//
+// fp32 inputs use the same bf16 main loop: every value is split into three bf16
+// parts (x = x0 + x1 + x2) and the six leading cross products are laid side by
+// side along the contraction index, which recovers fp32-grade logits.
+#include <algorithm>
+
+#include "gemm_core.hpp"
+#include "pg_common.hpp"
+
+namespace spo {
+
+typedef Tile<256, 256, 2, 4> TL;  // 8 wavefronts, each a 128 x 64 part of the tile
+constexpr int kSplitTerms = 6;    // cross products kept by the fp32 split
+constexpr int64_t kDefaultChunk = 32768;
+
+// ----------------------------------------------------------------------------
+// operand preparation
+// ----------------------------------------------------------------------------
+
+// dst[r][j*K + k] = part_{sel(j)}(src[r][k]) with sel = {0,0,1,0,2,1} (side 0) or
+// {0,1,0,2,0,1} (side 1): sum_j dst0[.][jK+k] * dst1[.][jK+k] keeps the products
+// x0y0, x0y1, x1y0, x0y2, x2y0, x1y1 of the three-part bf16 splits of x and y.
+__global__ void __launch_bounds__(256)
+split_expand_kernel(const float *__restrict__ src, int64_t rows, int64_t K, bf16_t *__restrict__ dst, int side) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= rows * K) return;
+    const int64_t r = i / K, k = i % K;
+    const float x = src[i];
+    const bf16_t p0 = f32_to_bf16(x);
+    const float r1 = x - bf16_to_f32(p0);
+    const bf16_t p1 = f32_to_bf16(r1);
+    const bf16_t p2 = f32_to_bf16(r1 - bf16_to_f32(p1));
+    bf16_t *o = dst + r * (kSplitTerms * K) + k;
+    if (side == 0) {
+        o[0] = p0; o[K] = p0; o[2 * K] = p1; o[3 * K] = p0; o[4 * K] = p2; o[5 * K] = p1;
+    } else {
+        o[0] = p0; o[K] = p1; o[2 * K] = p0; o[3 * K] = p2; o[4 * K] = p0; o[5 * K] = p1;
+    }
+}
+
+__device__ __forceinline__ bf16_t load_as_bf16(const bf16_t *p) { return *p; }
+__device__ __forceinline__ bf16_t load_as_bf16(const float *p) { return f32_to_bf16(*p); }
+
+// dst[c][r] = bf16(src[r][c]) for r < R, c < C; dst[c][r] = 0 for R <= r < R_pad and
+// for C <= c < C_pad (all r < R_pad).  dst has leading dimension ld_dst >= R_pad.
+template <typename SrcT>
+__global__ void __launch_bounds__(256)
+transpose_to_bf16_kernel(const SrcT *__restrict__ src, int64_t R, int64_t C, int64_t ld_src,
+                         bf16_t *__restrict__ dst, int64_t R_pad, int64_t C_pad, int64_t ld_dst) {
+    __shared__ bf16_t tile[64][66];
+    const int64_t r0 = static_cast<int64_t>(blockIdx.x) * 64, c0 = static_cast<int64_t>(blockIdx.y) * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int i = ty; i < 64; i += 4) {
+        const int64_t r = r0 + i, c = c0 + tx;
+        tile[i][tx] = (r < R && c < C) ? load_as_bf16(src + r * ld_src + c) : bf16_t(0);
+    }
+    __syncthreads();
+    for (int i = ty; i < 64; i += 4) {
+        const int64_t c = c0 + i, r = r0 + tx;
+        if (c < C_pad && r < R_pad) dst[c * ld_dst + r] = tile[tx][i];
+    }
+}
+
+__global__ void __launch_bounds__(256)
+f32_to_bf16_kernel(const float *__restrict__ src, bf16_t *__restrict__ dst, int64_t n) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i < n) dst[i] = f32_to_bf16(src[i]);
+}
+
+__global__ void __launch_bounds__(256) fill_zero_kernel(uint32_t *__restrict__ p, int64_t n_words) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i < n_words) p[i] = 0u;
+}
+
+// ----------------------------------------------------------------------------
+// forward: vocabulary sweep with online log-sum-exp and target capture
+// ----------------------------------------------------------------------------
+// Tile rows (m) are vocabulary entries, tile columns (n) are tokens, so that each
+// lane owns FN tokens and reduces over the vocabulary inside its own registers.
+// Workgroup (token tile jt, vocabulary split r) walks the vocabulary tiles of its
+// split; ids equal mod 8 (same XCD, same L2) hold the splits of the same few
+// token tiles, which then share hidden-state panels in that L2.
+__global__ void __launch_bounds__(TL::NT)
+fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const char *__restrict__ X,
+                 int64_t ldx_bytes, int64_t T, int KT, const int32_t *__restrict__ target, int nsplit,
+                 int64_t nTt, int64_t nVt, int64_t T_pad, float *__restrict__ part_max,
+                 float *__restrict__ part_sum, float *__restrict__ z_target) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int64_t bid = blockIdx.x, xcd = bid & 7, q = bid >> 3;
+    const int split = static_cast<int>(q % nsplit);
+    const int64_t jt = (q / nsplit) * 8 + xcd;
+    if (jt >= nTt) return;
+    const int64_t n0 = jt * TL::BN;
+    const int64_t vt0 = split * nVt / nsplit, vt1 = (split + 1) * nVt / nsplit;
+    const int lane = threadIdx.x & 63;
+
+    float m_run[TL::FN], s_run[TL::FN];
+    int32_t tgt[TL::FN];
+#pragma unroll
+    for (int fn = 0; fn < TL::FN; ++fn) {
+        m_run[fn] = kNegBig;
+        s_run[fn] = 0.0f;
+        const int64_t t = n0 + TL::acc_col(fn);
+        tgt[fn] = t < T ? target[t] : -1;
+    }
+    for (int64_t vt = vt0; vt < vt1; ++vt) {
+        const int64_t m0 = vt * TL::BM;
+        TL::Acc acc;
+        TL::zero(acc);
+        TL::mainloop(W, ldw_bytes, m0, V, X, ldx_bytes, n0, T, KT, lds, acc);
+        if (m0 + TL::BM > V) {  // ragged last tile: rows past the vocabulary do not count
+#pragma unroll
+            for (int fm = 0; fm < TL::FM; ++fm)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (m0 + TL::acc_row(fm, r) >= V)
+#pragma unroll
+                        for (int fn = 0; fn < TL::FN; ++fn) acc[fm][fn][r] = kNegBig;
+        }
+#pragma unroll
+        for (int fn = 0; fn < TL::FN; ++fn) {
+            float mx = kNegBig;
+#pragma unroll
+            for (int fm = 0; fm < TL::FM; ++fm)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc[fm][fn][r]);
+            const float nm = fmaxf(m_run[fn], mx);
+            const float nm2 = -nm * kLog2e;
+            float s = 0.0f;
+#pragma unroll
+            for (int fm = 0; fm < TL::FM; ++fm)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s += __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r], kLog2e, nm2));
+            s_run[fn] = s_run[fn] * __builtin_amdgcn_exp2f((m_run[fn] - nm) * kLog2e) + s;
+            m_run[fn] = nm;
+            // the sampled token's logit, if its vocabulary row is one of mine
+            const int d = tgt[fn] - static_cast<int>(m0 + TL::wave_m0());
+            if (static_cast<unsigned>(d) < static_cast<unsigned>(TL::WM) && ((d >> 2) & 1) == (lane >> 5)) {
+                const int fq = d >> 5, rq = ((d & 31) >> 3) * 4 + (d & 3);
+                float z = 0.0f;
+#pragma unroll
+                for (int fm = 0; fm < TL::FM; ++fm)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (fm == fq && r == rq) z = acc[fm][fn][r];
+                z_target[n0 + TL::acc_col(fn)] = z;
+            }
+        }
+    }
+    // merge the two lane halves, then the WGM wavefronts that share a token column
+    float *red_m = reinterpret_cast<float *>(lds);
+    float *red_s = red_m + TL::WGM * TL::BN;
+    __syncthreads();  // operand stages are no longer read
+#pragma unroll
+    for (int fn = 0; fn < TL::FN; ++fn) {
+        const float om = __shfl_xor(m_run[fn], 32, kWave), os = __shfl_xor(s_run[fn], 32, kWave);
+        const float nm = fmaxf(m_run[fn], om);
+        const float s = s_run[fn] * __builtin_amdgcn_exp2f((m_run[fn] - nm) * kLog2e) +
+                        os * __builtin_amdgcn_exp2f((om - nm) * kLog2e);
+        if (lane < 32) {
+            const int slot = (TL::wave_id() % TL::WGM) * TL::BN + TL::acc_col(fn);
+            red_m[slot] = nm;
+            red_s[slot] = s;
+        }
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < TL::BN; c += TL::NT) {
+        float nm = kNegBig;
+#pragma unroll
+        for (int w = 0; w < TL::WGM; ++w) nm = fmaxf(nm, red_m[w * TL::BN + c]);
+        float s = 0.0f;
+#pragma unroll
+        for (int w = 0; w < TL::WGM; ++w)
+            s += red_s[w * TL::BN + c] * __builtin_amdgcn_exp2f((red_m[w * TL::BN + c] - nm) * kLog2e);
+        part_max[split * T_pad + n0 + c] = nm;
+        part_sum[split * T_pad + n0 + c] = s;
+    }
+}
+
+// ----------------------------------------------------------------------------
+// backward, step 1: recompute a logits tile and emit its bf16 gradient
+// ----------------------------------------------------------------------------
+// dz[t][v] = g[t] * ([v == target[t]] - exp(z[t][v] - lse[t])), written both as
+// dZ[t][v] (row stride ldz, vocabulary contiguous: operand of dHidden) and as
+// dZT[v][t] (row stride ldzt, tokens contiguous: operand of dW).  Columns
+// V <= v < V_pad of dZ and tokens past T_valid are written as zeros.
+__global__ void __launch_bounds__(TL::NT)
+recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, int64_t V_pad,
+                    const char *__restrict__ X, int64_t ldx_bytes, int64_t T_valid, int KT,
+                    const int32_t *__restrict__ target, const float *__restrict__ lse,
+                    const float *__restrict__ g, int64_t nVt, int64_t nTt, bf16_t *__restrict__ dZ,
+                    int64_t ldz, bf16_t *__restrict__ dZT, int64_t ldzt) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    int64_t tm, tn;
+    if (!TileOrder(nVt, nTt).tile(blockIdx.x, tm, tn)) return;
+    const int64_t m0 = tm * TL::BM, n0 = tn * TL::BN;
+    TL::Acc acc;
+    TL::zero(acc);
+    TL::mainloop(W, ldw_bytes, m0, V, X, ldx_bytes, n0, T_valid, KT, lds, acc);
+#pragma unroll
+    for (int fn = 0; fn < TL::FN; ++fn) {
+        const int64_t t = n0 + TL::acc_col(fn);
+        const bool tok_ok = t < T_valid;
+        const float gt = tok_ok ? g[t] : 0.0f;
+        const float nl = tok_ok ? -lse[t] * kLog2e : 0.0f;
+        const int32_t y = tok_ok ? target[t] : -1;
+#pragma unroll
+        for (int fm = 0; fm < TL::FM; ++fm) {
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const int64_t v0 = m0 + TL::acc_row(fm, r4 * 4);
+                float dz[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int64_t v = v0 + i;
+                    const float p = __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r4 * 4 + i], kLog2e, nl));
+                    float x = (v == y ? gt : 0.0f) - gt * p;
+                    dz[i] = (gt != 0.0f && v < V) ? x : 0.0f;
+                }
+                if (dZ && v0 < V_pad) {
+                    uint2 pk;
+                    pk.x = pack_bf16x2(dz[0], dz[1]);
+                    pk.y = pack_bf16x2(dz[2], dz[3]);
+                    *reinterpret_cast<uint2 *>(dZ + t * ldz + v0) = pk;
+                }
+                if (dZT) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (v0 + i < V) dZT[(v0 + i) * ldzt + t] = f32_to_bf16(dz[i]);
+                }
+            }
+        }
+    }
+}
+
+// ----------------------------------------------------------------------------
+// backward, steps 2 and 3: plain contraction with a store / accumulate epilogue
+// ----------------------------------------------------------------------------
+// out[m*ldo + n] (=|+=) sum_k A[m][k] B[n][k]
+__global__ void __launch_bounds__(TL::NT)
+gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, const char *__restrict__ B,
+                  int64_t ldb_bytes, int64_t N, int KT, void *__restrict__ out, int64_t ldo, int out_dtype,
+                  int accumulate) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    int64_t tm, tn;
+    if (!TileOrder(ceil_div(M, TL::BM), ceil_div(N, TL::BN)).tile(blockIdx.x, tm, tn)) return;
+    const int64_t m0 = tm * TL::BM, n0 = tn * TL::BN;
+    TL::Acc acc;
+    TL::zero(acc);
+    TL::mainloop(A, lda_bytes, m0, M, B, ldb_bytes, n0, N, KT, lds, acc);
+#pragma unroll
+    for (int fn = 0; fn < TL::FN; ++fn) {
+        const int64_t n = n0 + TL::acc_col(fn);
+        if (n >= N) continue;
+#pragma unroll
+        for (int fm = 0; fm < TL::FM; ++fm)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t m = m0 + TL::acc_row(fm, r);
+                if (m >= M) continue;
+                if (out_dtype == SPO_FP32) {
+                    float *o = static_cast<float *>(out) + m * ldo + n;
+                    *o = accumulate ? *o + acc[fm][fn][r] : acc[fm][fn][r];
+                } else {
+                    static_cast<bf16_t *>(out)[m * ldo + n] = f32_to_bf16(acc[fm][fn][r]);
+                }
+            }
+    }
+}
+
+// ----------------------------------------------------------------------------
+// host side
+// ----------------------------------------------------------------------------
+static int set_lds_limit() {
+    static bool done = false;
+    static int status = SPO_OK;
+    if (!done) {
+        hipError_t e = hipSuccess;
+        e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_sweep_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
+        e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(recompute_dz_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
+        e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_store_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
+        status = e == hipSuccess ? SPO_OK : SPO_EHIP;
+        done = true;
+    }
+    return status;
+}
+
+static inline int64_t round_up(int64_t x, int64_t a) { return ceil_div(x, a) * a; }
+static inline unsigned grid1(int64_t n, int per = 256) { return static_cast<unsigned>(ceil_div(n, per)); }
+
+struct FwdPlan {
+    int64_t nTt, nVt, T_pad, Kc;  // Kc: contraction length seen by the main loop
+    int nsplit;
+    int64_t nblk_tok;
+    // workspace
+    float *part_max, *part_sum, *z_target;
+    FwdPartial *partials;
+    bf16_t *Xs, *Ws, *Wvh;  // split-expanded operands (fp32), [V,H] copy (HV layout)
+    size_t bytes;
+};
+
+static FwdPlan plan_fwd(const spo_pg_desc *d, void *ws) {
+    FwdPlan p;
+    p.nTt = ceil_div(d->T, TL::BN);
+    p.nVt = ceil_div(d->V, TL::BM);
+    p.T_pad = p.nTt * TL::BN;
+    int64_t ns = std::max<int64_t>(8, ceil_div(2048, std::max<int64_t>(p.nTt, 1)));
+    p.nsplit = static_cast<int>(std::min<int64_t>(ns, p.nVt));
+    p.Kc = d->dtype == SPO_FP32 ? kSplitTerms * d->H : d->H;
+    p.nblk_tok = ceil_div(std::max<int64_t>(d->T, 1), kTokThreads);
+    Arena a(ws);
+    p.part_max = a.take<float>(static_cast<size_t>(p.nsplit) * p.T_pad);
+    p.part_sum = a.take<float>(static_cast<size_t>(p.nsplit) * p.T_pad);
+    p.z_target = a.take<float>(p.T_pad);
+    p.partials = a.take<FwdPartial>(p.nblk_tok);
+    p.Xs = p.Ws = p.Wvh = nullptr;
+    if (d->dtype == SPO_FP32) {
+        p.Xs = a.take<bf16_t>(static_cast<size_t>(std::max<int64_t>(d->T, 1)) * p.Kc);
+        p.Ws = a.take<bf16_t>(static_cast<size_t>(d->V) * p.Kc);
+    } else if (d->w_layout == SPO_W_HV) {
+        p.Wvh = a.take<bf16_t>(static_cast<size_t>(d->V) * d->H);
+    }
+    p.bytes = a.used;
+    return p;
+}
+
+static int check_fused(const spo_pg_desc *d) {
+    if (d->dtype == SPO_FP32 && d->w_layout == SPO_W_HV) return SPO_EUNSUPPORTED;
+    if (reinterpret_cast<uintptr_t>(d->hidden) % 16 || reinterpret_cast<uintptr_t>(d->W) % 16) return SPO_EINVAL;
+    return SPO_OK;
+}
+
+int fused_fwd_workspace(const spo_pg_desc *d, size_t *bytes) {
+    *bytes = plan_fwd(d, nullptr).bytes;
+    return SPO_OK;
+}
+
+int fused_fwd(const spo_pg_desc *d, float *loss, float *logp, float *lse, float *stats, void *ws,
+              size_t ws_bytes, hipStream_t s) {
+    int rc = check_fused(d);
+    if (rc) return rc;
+    const FwdPlan p = plan_fwd(d, ws);
+    if (ws_bytes < p.bytes) return SPO_EWORKSPACE;
+    if ((rc = set_lds_limit())) return rc;
+    if (d->T > 0) {
+        const char *X, *W;
+        if (d->dtype == SPO_FP32) {
+            split_expand_kernel<<<grid1(d->T * d->H), 256, 0, s>>>(static_cast<const float *>(d->hidden), d->T, d->H, p.Xs, 1);
+            split_expand_kernel<<<grid1(d->V * d->H), 256, 0, s>>>(static_cast<const float *>(d->W), d->V, d->H, p.Ws, 0);
+            X = reinterpret_cast<const char *>(p.Xs);
+            W = reinterpret_cast<const char *>(p.Ws);
+        } else {
+            X = static_cast<const char *>(d->hidden);
+            if (d->w_layout == SPO_W_HV) {
+                transpose_to_bf16_kernel<bf16_t><<<dim3(grid1(d->H, 64), grid1(d->V, 64)), 256, 0, s>>>(
+                    static_cast<const bf16_t *>(d->W), d->H, d->V, d->V, p.Wvh, d->H, d->V, d->H);
+                W = reinterpret_cast<const char *>(p.Wvh);
+            } else {
+                W = static_cast<const char *>(d->W);
+            }
+        }
+        const int64_t blocks = ceil_div(p.nTt, 8) * 8 * p.nsplit;
+        fwd_sweep_kernel<<<static_cast<unsigned>(blocks), TL::NT, TL::LDS_BYTES, s>>>(
+            W, p.Kc * 2, d->V, X, p.Kc * 2, d->T, static_cast<int>(p.Kc / kBK), d->target, p.nsplit, p.nTt, p.nVt,
+            p.T_pad, p.part_max, p.part_sum, p.z_target);
+    }
+    token_loss_kernel<<<static_cast<unsigned>(p.nblk_tok), kTokThreads, 0, s>>>(
+        p.part_max, p.part_sum, p.nsplit, p.T_pad, p.z_target, d->T, d->old_logp, d->mask, d->adv_norm,
+        d->cu_seqlens, d->B, d->eps_low, d->eps_high, logp, lse, p.partials);
+    loss_finalize_kernel<<<1, kTokThreads, 0, s>>>(p.partials, p.nblk_tok, loss, stats);
+    return launch_status();
+}
+
+struct BwdPlan {
+    int64_t Tc, V_pad, Kc, T_pad;
+    double *count;
+    float *g, *dW_acc;
+    bf16_t *WT, *XT, *dZ, *dZT, *Xs, *Ws, *Wvh;
+    size_t bytes;
+};
+
+static BwdPlan plan_bwd(const spo_pg_desc *d, int64_t chunk_tokens, void *ws, bool need_dw_acc) {
+    BwdPlan p;
+    const int64_t Tmax = round_up(std::max<int64_t>(d->T, 1), TL::BN);
+    int64_t tc = chunk_tokens > 0 ? chunk_tokens : kDefaultChunk;
+    p.Tc = std::min(round_up(tc, TL::BN), Tmax);
+    p.T_pad = Tmax;
+    p.V_pad = round_up(d->V, kBK);
+    p.Kc = d->dtype == SPO_FP32 ? kSplitTerms * d->H : d->H;
+    Arena a(ws);
+    p.count = a.take<double>(1);
+    p.g = a.take<float>(p.T_pad);
+    p.WT = a.take<bf16_t>(static_cast<size_t>(d->H) * p.V_pad);
+    p.XT = a.take<bf16_t>(static_cast<size_t>(d->H) * p.Tc);
+    p.dZ = a.take<bf16_t>(static_cast<size_t>(p.Tc) * p.V_pad);
+    p.dZT = a.take<bf16_t>(static_cast<size_t>(d->V) * p.Tc);
+    p.Xs = p.Ws = p.Wvh = nullptr;
+    p.dW_acc = nullptr;
+    if (d->dtype == SPO_FP32) {
+        p.Xs = a.take<bf16_t>(static_cast<size_t>(p.Tc) * p.Kc);
+        p.Ws = a.take<bf16_t>(static_cast<size_t>(d->V) * p.Kc);
+    } else if (d->w_layout == SPO_W_HV) {
+        p.Wvh = a.take<bf16_t>(static_cast<size_t>(d->V) * d->H);
+    }
+    if (need_dw_acc) p.dW_acc = a.take<float>(static_cast<size_t>(d->V) * d->H);
+    p.bytes = a.used;
+    return p;
+}
+
+int fused_bwd_workspace(const spo_pg_desc *d, int64_t chunk_tokens, size_t *bytes) {
+    // sized for the larger case (bf16 d_W needs an fp32 accumulator)
+    *bytes = plan_bwd(d, chunk_tokens, nullptr, true).bytes;
+    return SPO_OK;
+}
+
+template <typename SrcT>
+static void launch_transpose(const SrcT *src, int64_t R, int64_t C, int64_t ld_src, bf16_t *dst, int64_t R_pad,
+                             int64_t C_pad, int64_t ld_dst, hipStream_t s) {
+    transpose_to_bf16_kernel<SrcT><<<dim3(grid1(R_pad, 64), grid1(C_pad, 64)), 256, 0, s>>>(src, R, C, ld_src, dst,
+                                                                                         R_pad, C_pad, ld_dst);
+}
+
+static void launch_gemm(const bf16_t *A, int64_t lda, int64_t M, const bf16_t *B, int64_t ldb, int64_t N, int64_t K,
+                        void *out, int64_t ldo, int out_dtype, int accumulate, hipStream_t s) {
+    const TileOrder ord(ceil_div(M, TL::BM), ceil_div(N, TL::BN));
+    gemm_store_kernel<<<static_cast<unsigned>(ord.blocks()), TL::NT, TL::LDS_BYTES, s>>>(
+        reinterpret_cast<const char *>(A), lda * 2, M, reinterpret_cast<const char *>(B), ldb * 2, N,
+        static_cast<int>(K / kBK), out, ldo, out_dtype, accumulate);
+}
+
+int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float grad_loss, void *d_hidden,
+              int d_hidden_dtype, void *d_W, int d_W_dtype, int accumulate_dW, int64_t chunk_tokens, void *ws,
+              size_t ws_bytes, hipStream_t s) {
+    int rc = check_fused(d);
+    if (rc) return rc;
+    if (accumulate_dW && d_W && d_W_dtype != SPO_FP32) return SPO_EINVAL;
+    const bool need_acc = d_W && d_W_dtype == SPO_BF16;
+    const BwdPlan p = plan_bwd(d, chunk_tokens, ws, need_acc);
+    if (ws_bytes < p.bytes) return SPO_EWORKSPACE;
+    if ((rc = set_lds_limit())) return rc;
+    const int64_t H = d->H, V = d->V, T = d->T;
+    float *dW32 = need_acc ? p.dW_acc : static_cast<float *>(d_W);
+    if (T == 0) {
+        if (d_W && !accumulate_dW) {
+            const int64_t words = d_W_dtype == SPO_FP32 ? V * H : V * H / 2;
+            fill_zero_kernel<<<grid1(words), 256, 0, s>>>(static_cast<uint32_t *>(d_W), words);
+        }
+        return launch_status();
+    }
+    mask_count_kernel<<<1, 1024, 0, s>>>(d->mask, T, p.count);
+    grad_scale_kernel<<<grid1(p.T_pad, kTokThreads), kTokThreads, 0, s>>>(
+        logp, d->old_logp, d->mask, d->adv_norm, d->cu_seqlens, d->B, T, p.T_pad, d->eps_low, d->eps_high, grad_loss,
+        p.count, p.g);
+    // vocabulary-major head for the recompute, hidden-major head for dHidden
+    const bf16_t *Wk;
+    if (d->dtype == SPO_FP32) {
+        split_expand_kernel<<<grid1(V * H), 256, 0, s>>>(static_cast<const float *>(d->W), V, H, p.Ws, 0);
+        Wk = p.Ws;
+        if (d_hidden) launch_transpose(static_cast<const float *>(d->W), V, H, H, p.WT, p.V_pad, H, p.V_pad, s);
+    } else {
+        const bf16_t *Wvh = static_cast<const bf16_t *>(d->W);
+        if (d->w_layout == SPO_W_HV) {
+            launch_transpose(static_cast<const bf16_t *>(d->W), H, V, V, p.Wvh, H, V, H, s);
+            Wvh = p.Wvh;
+        }
+        Wk = Wvh;
+        if (d_hidden) launch_transpose(Wvh, V, H, H, p.WT, p.V_pad, H, p.V_pad, s);
+    }
+    const int64_t nVt = ceil_div(V, TL::BM);
+    for (int64_t t0 = 0, c = 0; t0 < T; t0 += p.Tc, ++c) {
+        const int64_t Tv = std::min(p.Tc, T - t0), Tcp = round_up(Tv, TL::BN);
+        const bf16_t *Xk;
+        if (d->dtype == SPO_FP32) {
+            const float *xs = static_cast<const float *>(d->hidden) + t0 * H;
+            split_expand_kernel<<<grid1(Tv * H), 256, 0, s>>>(xs, Tv, H, p.Xs, 1);
+            Xk = p.Xs;
+            if (d_W) launch_transpose(xs, Tv, H, H, p.XT, Tcp, H, p.Tc, s);
+        } else {
+            const bf16_t *xs = static_cast<const bf16_t *>(d->hidden) + t0 * H;
+            Xk = xs;
+            if (d_W) launch_transpose(xs, Tv, H, H, p.XT, Tcp, H, p.Tc, s);
+        }
+        const TileOrder ord(nVt, Tcp / TL::BN);
+        recompute_dz_kernel<<<static_cast<unsigned>(ord.blocks()), TL::NT, TL::LDS_BYTES, s>>>(
+            reinterpret_cast<const char *>(Wk), p.Kc * 2, V, p.V_pad, reinterpret_cast<const char *>(Xk), p.Kc * 2, Tv,
+            static_cast<int>(p.Kc / kBK), d->target + t0, lse + t0, p.g + t0, nVt, Tcp / TL::BN,
+            d_hidden ? p.dZ : nullptr, p.V_pad, d_W ? p.dZT : nullptr, p.Tc);
+        if (d_hidden) {
+            char *dx = static_cast<char *>(d_hidden) + t0 * H * (d_hidden_dtype == SPO_FP32 ? 4 : 2);
+            launch_gemm(p.dZ, p.V_pad, Tv, p.WT, p.V_pad, H, p.V_pad, dx, H, d_hidden_dtype, 0, s);
+        }
+        if (d_W) {
+            const int acc = (c > 0 || accumulate_dW) ? 1 : 0;
+            if (d->w_layout == SPO_W_VH)
+                launch_gemm(p.dZT, p.Tc, V, p.XT, p.Tc, H, Tcp, dW32, H, SPO_FP32, acc, s);
+            else
+                launch_gemm(p.XT, p.Tc, H, p.dZT, p.Tc, V, Tcp, dW32, V, SPO_FP32, acc, s);
+        }
+    }
+    if (need_acc) f32_to_bf16_kernel<<<grid1(V * H), 256, 0, s>>>(p.dW_acc, static_cast<bf16_t *>(d_W), V * H);
+    return launch_status();
+}
+
+}  // namespace spo

@@ -1,0 +1,204 @@
+"""GPU parity of the clipped policy-gradient loss (fused LM-head form and
+logits-in form, forward and backward) against the fp64 oracle, through the C ABI.
+
+Tolerances: lse / logp absolute 2e-4 (bf16 inputs, fp32 accumulation), loss 2e-3
+relative, gradients 1e-2 relative L2; fp32 inputs: lse / logp absolute 2e-5."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2509_13232_amd import workloads as wl
+from pg_cases import Case, check_forward, f64, rel_l2, say
+
+pytestmark = pytest.mark.gpu
+GRAD_TOL = 1e-2
+
+
+@pytest.fixture(scope="module")
+def spo():
+    from paper_2509_13232_amd import binding
+    binding.lib()
+    assert torch.cuda.is_available()
+    return binding
+
+
+MID = wl.scaled(wl.CONFIGS["C2"], name="mid", H=256, V=3000, mask_span=(4, 40))
+MID_LENGTHS = [37, 300, 1, 255, 120]  # T = 713: three token tiles, ragged tail; V: 11 tiles + 184
+
+
+def run_fwd_bwd(spo, case, w_layout=0, chunk_tokens=0, dx_dtype=torch.float32, dw_dtype=torch.float32):
+    desc = case.to_gpu(spo, w_layout)
+    fwd = spo.spo_pg_loss_fwd(desc)
+    dx, dw = spo.spo_pg_loss_bwd(desc, fwd[1], fwd[2], 1.0, d_hidden_dtype=dx_dtype, d_W_dtype=dw_dtype,
+                                 chunk_tokens=chunk_tokens)
+    torch.cuda.synchronize()
+    if w_layout == 1:
+        dw = dw.t()
+    return fwd, dx, dw
+
+
+def test_tiny_spo_step_fp32(spo, oracle):
+    cfg = wl.CONFIGS["C1"]
+    say("fused fp32 C1 T=512 H=128 V=1000")
+    case = Case(cfg)
+    assert case.T == 512
+    case.set_old_from_oracle(oracle)
+    fwd, dx, dw = run_fwd_bwd(spo, case)
+    ref = check_forward(case, oracle, fwd, atol_logp=2e-5)
+    assert 0 < ref["active"].sum() < case.T          # both branches of the min occur
+    rb = oracle.pg_loss_bwd(*case.oracle_inputs(), *case.eps)
+    assert rel_l2(f64(dx), rb["d_hidden"]) < GRAD_TOL
+    assert rel_l2(f64(dw), rb["d_W"]) < GRAD_TOL
+
+
+@pytest.mark.parametrize("w_layout", [0, 1])
+@pytest.mark.parametrize("w_scale,mask_frac", [(1.0, 0.0), (1.0, 0.25), (30.0, 0.25)])
+def test_fused_bf16_matches_oracle(spo, oracle, w_layout, w_scale, mask_frac):
+    say(f"fused bf16 mid T=713 H=256 V=3000 w_layout={w_layout} w_scale={w_scale} mask={mask_frac}")
+    case = Case(MID, MID_LENGTHS, w_scale=w_scale, mask_frac=mask_frac)
+    case.set_old_from_oracle(oracle)
+    fwd, dx, dw = run_fwd_bwd(spo, case, w_layout)
+    check_forward(case, oracle, fwd)
+    rb = oracle.pg_loss_bwd(*case.oracle_inputs(), *case.eps)
+    assert rel_l2(f64(dx), rb["d_hidden"]) < GRAD_TOL
+    assert rel_l2(f64(dw), rb["d_W"]) < GRAD_TOL
+    # the softmax part alone (gradient minus the rank-one target term), which a flat
+    # softmax hides inside the total: bounded by the bf16 rounding of the logit
+    # gradients of both parts
+    g = rb["g"]
+    Wd, Hd = f64(case.W), f64(case.hidden)
+    onehot_dx = g[:, None] * Wd[case.target]
+    soft_ref = rb["d_hidden"] - onehot_dx
+    soft_gpu = f64(dx) - onehot_dx
+    bound = GRAD_TOL * np.linalg.norm(soft_ref) + 2.0 ** -8 * np.linalg.norm(onehot_dx)
+    assert np.linalg.norm(soft_gpu - soft_ref) <= bound
+    if w_scale > 1.0:   # peaked softmax: the softmax part is as large as the target part
+        assert np.linalg.norm(soft_ref) > 0.3 * np.linalg.norm(onehot_dx)
+        assert rel_l2(soft_gpu, soft_ref) < 2 * GRAD_TOL
+    # rows of masked tokens are exactly zero; softmax rows sum to one
+    if case.mask is not None:
+        assert not dx[torch.as_tensor(case.mask == 0)].any()
+    col = f64(dw).sum(axis=0)
+    assert np.abs(col).max() <= 2e-2 * np.abs(f64(dw)).sum(axis=0).max()
+    del Hd
+
+
+def test_backward_chunks_and_output_dtypes(spo, oracle):
+    say("fused bf16 mid, chunk_tokens=256 (3 chunks), bf16 outputs")
+    case = Case(MID, MID_LENGTHS, mask_frac=0.25)
+    case.set_old_from_oracle(oracle)
+    rb = oracle.pg_loss_bwd(*case.oracle_inputs(), *case.eps)
+    _, dx1, dw1 = run_fwd_bwd(spo, case, chunk_tokens=256)
+    _, dx2, dw2 = run_fwd_bwd(spo, case, chunk_tokens=0)
+    assert rel_l2(f64(dx1), rb["d_hidden"]) < GRAD_TOL and rel_l2(f64(dw1), rb["d_W"]) < GRAD_TOL
+    assert torch.equal(dx1, dx2)                       # rows do not depend on the chunking
+    assert rel_l2(f64(dw1), f64(dw2)) < 1e-5           # fp32 partial sums in another order
+    _, dx3, dw3 = run_fwd_bwd(spo, case, chunk_tokens=512, dx_dtype=torch.bfloat16, dw_dtype=torch.bfloat16)
+    assert dx3.dtype == torch.bfloat16 and dw3.dtype == torch.bfloat16
+    assert rel_l2(f64(dx3), rb["d_hidden"]) < GRAD_TOL and rel_l2(f64(dw3), rb["d_W"]) < GRAD_TOL
+
+
+def test_results_are_bitwise_reproducible(spo, oracle):
+    say("fused bf16 mid, determinism")
+    case = Case(MID, MID_LENGTHS)
+    case.set_old_from_oracle(oracle)
+    a = run_fwd_bwd(spo, case)
+    b = run_fwd_bwd(spo, case)
+    assert torch.equal(a[0][0], b[0][0]) and torch.equal(a[0][1], b[0][1])
+    assert torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])
+
+
+def test_mini_batches_accumulate_into_dW(spo, oracle):
+    # two mini-batches of whole responses, the batch-wide normalised advantages,
+    # gradients accumulated into one d_W (one optimiser step per mini-batch is the
+    # caller's business; the kernel only has to add)
+    say("fused bf16 mid, two mini-batches, accumulate_dW")
+    case = Case(MID, MID_LENGTHS)
+    case.set_old_from_oracle(oracle)
+    h, w, tg, old, mk, ad, cu = case.oracle_inputs()
+    d = "cuda"
+    hidden, W = case.hidden.to(d), case.W.to(d)
+    target = torch.as_tensor(case.target).to(d)
+    oldg = torch.as_tensor(case.old).to(d)
+    adv = torch.as_tensor(case.adv).to(d)
+    cug = torch.as_tensor(case.cu).to(d)
+    dW = torch.zeros_like(W, dtype=torch.float32)
+    ref_dw = np.zeros_like(w)
+    for (b0, b1) in ((0, 2), (2, 5)):
+        t0, t1 = int(cu[b0]), int(cu[b1])
+        desc = spo.make_desc(hidden[t0:t1], W, target[t0:t1], oldg[t0:t1], None, adv[b0:b1],
+                             cug[b0:b1 + 1], *case.eps)
+        loss, logp, lse, _ = spo.spo_pg_loss_fwd(desc)
+        dx, _ = spo.spo_pg_loss_bwd(desc, logp, lse, 1.0, d_hidden_dtype=torch.float32, d_W=dW,
+                                    accumulate_dW=True)
+        torch.cuda.synchronize()
+        sub_cu = (cu[b0:b1 + 1] - cu[b0]).astype(np.int32)
+        rf = oracle.pg_loss_fwd(h[t0:t1], w, tg[t0:t1], old[t0:t1], None, ad[b0:b1], sub_cu, *case.eps)
+        rb = oracle.pg_loss_bwd(h[t0:t1], w, tg[t0:t1], old[t0:t1], None, ad[b0:b1], sub_cu, *case.eps)
+        assert abs(loss.item() - rf["loss"]) <= 2e-3 * abs(rf["loss"]) + 1e-7
+        assert rel_l2(f64(dx), rb["d_hidden"]) < GRAD_TOL
+        ref_dw += rb["d_W"]
+    assert rel_l2(f64(dW), ref_dw) < GRAD_TOL
+
+
+def test_degenerate_inputs(spo, oracle):
+    say("fused: all tokens masked")
+    case = Case(MID, [40, 60], mask_frac=0.5)
+    case.set_old_from_oracle(oracle)
+    case.mask = np.zeros(case.T, np.uint8)
+    fwd, dx, dw = run_fwd_bwd(spo, case)
+    assert fwd[0].item() == 0.0 and not dx.any() and not dw.any()
+    ref = oracle.pg_loss_fwd(*case.oracle_inputs(), *case.eps)
+    np.testing.assert_allclose(f64(fwd[1]), ref["logp"], atol=2e-4)     # log-probs are still produced
+    say("fused: one token, vocabulary smaller than a tile")
+    tiny = wl.scaled(MID, name="tiny", H=64, V=100)
+    case = Case(tiny, [1], adv=[1.5])
+    case.set_old_from_oracle(oracle)
+    fwd, dx, dw = run_fwd_bwd(spo, case)
+    check_forward(case, oracle, fwd)
+    rb = oracle.pg_loss_bwd(*case.oracle_inputs(), *case.eps)
+    assert rel_l2(f64(dx), rb["d_hidden"]) < GRAD_TOL and rel_l2(f64(dw), rb["d_W"]) < GRAD_TOL
+    say("fused: empty responses inside the batch")
+    case = Case(MID, [0, 70, 0, 0, 33, 0])
+    case.set_old_from_oracle(oracle)
+    fwd, dx, dw = run_fwd_bwd(spo, case)
+    check_forward(case, oracle, fwd)
+    rb = oracle.pg_loss_bwd(*case.oracle_inputs(), *case.eps)
+    assert rel_l2(f64(dx), rb["d_hidden"]) < GRAD_TOL and rel_l2(f64(dw), rb["d_W"]) < GRAD_TOL
+    say("fused: no tokens at all")
+    case = Case(MID, [0, 0])
+    case.old = np.zeros(0, np.float32)
+    desc = case.to_gpu(spo)
+    loss, logp, lse, stats = spo.spo_pg_loss_fwd(desc)
+    dW = torch.full((MID.V, MID.H), 7.0, device="cuda")
+    spo.spo_pg_loss_bwd(desc, logp, lse, 1.0, d_W=dW, want_d_hidden=False)
+    torch.cuda.synchronize()
+    assert loss.item() == 0.0 and stats[0].item() == 0.0 and not dW.any()
+
+
+@pytest.mark.parametrize("dtype,V", [("bf16", 3000), ("bf16", 1001), ("fp32", 3000), ("fp32", 1001)])
+def test_logits_in_matches_oracle(spo, oracle, dtype, V):
+    say(f"logits-in {dtype} T=713 V={V}")
+    cfg = wl.scaled(MID, V=V, dtype=dtype)
+    case = Case(cfg, MID_LENGTHS, mask_frac=0.25)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    # the logits a model would hand over, rounded to the storage type: they are the input
+    logits = (case.hidden.float() @ case.W.float().t() * 4.0).to(tdt)
+    lg64 = f64(logits)
+    h, w, tg, _, mk, ad, cu = case.oracle_inputs()
+    logp = oracle.pg_loss_fwd(None, None, tg, np.zeros(case.T), mk, ad, cu, *case.eps, logits=lg64)["logp"]
+    old = (logp + case.noise).astype(np.float32)
+    ratio = np.exp(logp - old)
+    near = (np.abs(ratio - 0.8) < 2e-3) | (np.abs(ratio - 1.28) < 3e-3)
+    old[near] += np.float32(0.01)
+    case.old = old
+    ref = oracle.pg_loss_fwd(None, None, tg, old.astype(np.float64), mk, ad, cu, *case.eps, logits=lg64)
+    rb = oracle.pg_loss_bwd(None, None, tg, old.astype(np.float64), mk, ad, cu, *case.eps, logits=lg64)
+    desc = case.to_gpu(spo, logits=logits.cuda())
+    fwd = spo.spo_pg_loss_fwd(desc)
+    dl = spo.spo_pg_loss_bwd(desc, fwd[1], fwd[2], 1.0)
+    torch.cuda.synchronize()
+    check_forward(case, oracle, fwd, ref=ref, atol_logp=2e-5 if dtype == "fp32" else 2e-4,
+                  rtol_loss=2e-3)
+    assert rel_l2(f64(dl), rb["d_logits"]) < (1e-5 if dtype == "fp32" else GRAD_TOL)
+    assert not dl[torch.as_tensor(case.mask == 0)].any()
