@@ -136,12 +136,14 @@ fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const
 #pragma unroll
                 for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc[fm][fn][r]);
             const float nm = fmaxf(m_run[fn], mx);
-            const float nm2 = -nm * kLog2e;
             float s = 0.0f;
+            // subtract first: with every row masked nm is the sentinel itself and the
+            // difference must be an exact zero, which a fused multiply-add of two huge
+            // rounded products would not give
 #pragma unroll
             for (int fm = 0; fm < TL::FM; ++fm)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s += __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r], kLog2e, nm2));
+                for (int r = 0; r < 16; ++r) s += __builtin_amdgcn_exp2f((acc[fm][fn][r] - nm) * kLog2e);
             s_run[fn] = s_run[fn] * __builtin_amdgcn_exp2f((m_run[fn] - nm) * kLog2e) + s;
             m_run[fn] = nm;
             // the sampled token's logit, if its vocabulary row is one of mine
