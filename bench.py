@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Throughput of the SPO hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic batch: prioritized
+sampling -> advantages -> tracker update -> fused LM-head + clipped
+policy-gradient loss forward -> backward (dHidden, dW).  Default workload: the
+Qwen3-8B head shape (H=4096, V=151936, bf16), 128 packed variable-length
+responses (~280k tokens).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3|C2|C4]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="C3", choices=["C2", "C3", "C4"])
+    ap.add_argument("--chunk-tokens", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-logits-in", action="store_true")
+    ap.add_argument("--cpu-tokens", type=int, default=128)
+    ap.add_argument("--calibrate-copy", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py measures one GPU: the path is built and measured on a single MI355X "
+            "(it shards by responses; see DESIGN.md). Run with --gpus 1.")
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2509_13232_amd import binding as spo
+    from paper_2509_13232_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        log("bench.py needs a GPU")
+        return 2
+    spo.lib()
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    cfg = wl.CONFIGS[args.workload]
+    t_setup = time.time()
+
+    # ---------------------------------------------------------------- inputs, resident in HBM
+    a0, b0 = wl.tracker_state(cfg)
+    alpha, beta = torch.as_tensor(a0).to(dev), torch.as_tensor(b0).to(dev)
+    tb = wl.token_batch(cfg, device=dev)
+    T, H, V, B = tb.T, cfg.H, cfg.V, cfg.B
+    target = torch.as_tensor(tb.target).to(dev)
+    cu = torch.as_tensor(tb.cu_seqlens).to(dev)
+    mask = None if tb.mask is None else torch.as_tensor(tb.mask).to(dev)
+    old_logp = wl.behaviour_logp_standin(tb.hidden, tb.W, tb.target, cfg.w_std, tb.noise)
+    idx0 = wl.distinct_indices(cfg, B)
+    reward = torch.as_tensor(wl.rewards(cfg, idx0)).to(dev)
+    kl = torch.as_tensor(wl.kl_divergences(cfg, B)).to(dev)
+    M = T if tb.mask is None else int(tb.mask.sum())
+    log(f"[bench] workload {cfg.name}: T={T} B={B} H={H} V={V} N={cfg.N} unmasked={M} "
+        f"(setup {time.time() - t_setup:.1f}s)")
+
+    # ---------------------------------------------------------------- preallocated outputs / workspaces
+    adv_holder = torch.zeros(B, dtype=torch.float32, device=dev)
+    desc = spo.make_desc(tb.hidden, tb.W, target, old_logp, mask, adv_holder, cu, cfg.eps_low, cfg.eps_high)
+    ws_s = torch.empty(spo.lib().spo_sample_prompts_workspace_bytes(cfg.N, B), dtype=torch.uint8, device=dev)
+    import ctypes as C
+    ws_f = torch.empty(max(256, spo.lib().spo_pg_loss_fwd_workspace_bytes(C.byref(desc[0]))), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(max(256, spo.spo_pg_loss_bwd_workspace_bytes(desc, args.chunk_tokens)), dtype=torch.uint8, device=dev)
+    d_W = torch.empty((V, H), dtype=torch.float32, device=dev)
+    log(f"[bench] workspaces: fwd {ws_f.numel() / 2**30:.2f} GiB, bwd {ws_b.numel() / 2**30:.2f} GiB")
+    state = {"loss": None, "stats": None}
+
+    def step(it: int):
+        idx = spo.spo_sample_prompts(alpha, beta, B, cfg.eps_explore, cfg.sample_seed, it, workspace=ws_s)
+        _, adv, _ = spo.spo_advantages(alpha, beta, idx, reward)
+        spo.spo_tracker_update(alpha, beta, idx, reward, kl, cfg.d_half, cfg.rho_min, cfg.rho_max)
+        adv_holder.copy_(adv)   # the descriptor points at adv_holder
+        loss, logp, lse, stats = spo.spo_pg_loss_fwd(desc, workspace=ws_f)
+        spo.spo_pg_loss_bwd(desc, logp, lse, 1.0, d_W=d_W, chunk_tokens=args.chunk_tokens, workspace=ws_b)
+        state["loss"], state["stats"] = loss, stats
+
+    if args.calibrate_copy:
+        # a plain elementwise copy of known size (1 GiB read, 1 GiB written) whose hardware
+        # counters calibrate the FETCH_SIZE / WRITE_SIZE readings of the other kernels
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 0.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+
+    for w in range(args.warmup):
+        step(w)
+    torch.cuda.synchronize()
+    spo.spo_kernel_timing_read()
+    spo.spo_kernel_timing_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(args.warmup + k)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    spo.spo_kernel_timing_enable(False)
+    times = spo.spo_kernel_timing_read()
+    sec = (t1 - t0) / args.steps
+    tok_s = T / sec
+    stats = state["stats"].cpu().tolist()
+    log(f"[bench] {sec * 1e3:.1f} ms/step, loss {state['loss'].item():.6f}, clipped share {stats[1]:.4f}, "
+        f"mean ratio {stats[2]:.4f}")
+
+    # ---------------------------------------------------------------- roofline of the dominant kernel
+    thv = 2.0 * T * H * V   # flops of one [T x H] x [H x V] contraction
+    kern = {}
+    for name in ("fwd_sweep", "bwd_recompute", "bwd_dhidden", "bwd_dw"):
+        ms, n = times[name]
+        if n:
+            per_step_ms = ms / args.steps
+            kern[name] = {"ms_per_step": round(per_step_ms, 3), "launches_per_step": n // args.steps,
+                          "avg_launch_ms": round(ms / n, 4),
+                          "tflops": round(thv / (per_step_ms * 1e-3) / 1e12, 1)}
+    dom = max(kern, key=lambda k: kern[k]["ms_per_step"])
+    ms_dom, n_dom = times[dom]
+    flops_per_launch = thv * args.steps / n_dom
+    achieved = flops_per_launch / (ms_dom / n_dom * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "flops_per_launch": flops_per_launch, "avg_launch_ms": round(ms_dom / n_dom, 4),
+                "kernels": kern}
+
+    out = {
+        "metric": "tokens/sec fused LM-head+SPO PG loss fwd+bwd at H=4096,V=151936; MFMA util %",
+        "value": round(tok_s, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {B} packed responses, lengths {cfg.lengths}, T={T} tokens, "
+                               f"H={H}, V={V}, {cfg.N}-prompt tracker, mask {cfg.mask_frac}",
+                   "T": T, "B": B, "H": H, "V": V, "N": cfg.N, "eps": [cfg.eps_low, cfg.eps_high],
+                   "d_half": cfg.d_half, "chunk_tokens": args.chunk_tokens or 32768},
+        "tflops_useful": round(3 * thv / sec / 1e12, 1),      # fwd + dHidden + dW
+        "tflops_executed": round(4 * thv / sec / 1e12, 1),    # + the backward's recompute
+        "mfma_util_executed": round(4 * thv / sec / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "clipped_share": round(stats[1], 5),
+        "roofline": roofline,
+    }
+
+    # ---------------------------------------------------------------- logits-in variant (HBM bound)
+    if not args.no_logits_in:
+        Tl = min(T, 8192)
+        del ws_b, d_W
+        torch.cuda.empty_cache()
+        logits = torch.empty((Tl, V), dtype=torch.bfloat16, device=dev)
+        for s in range(0, Tl, 1024):
+            logits[s:s + 1024] = tb.hidden[s:s + 1024] @ tb.W.t()   # input preparation, not timed
+        lcu = torch.tensor([0, Tl], dtype=torch.int32, device=dev)
+        ladv = torch.ones(1, dtype=torch.float32, device=dev)
+        ldesc = spo.make_desc(None, None, target[:Tl], old_logp[:Tl], None, ladv, lcu, cfg.eps_low, cfg.eps_high,
+                              logits=logits)
+        _, llogp, llse, _ = spo.spo_pg_loss_fwd(ldesc)
+        spo.spo_pg_loss_bwd(ldesc, llogp, llse, 1.0)
+        torch.cuda.synchronize()
+        spo.spo_kernel_timing_read()
+        spo.spo_kernel_timing_enable(True)
+        reps = 5
+        for _ in range(reps):
+            _, llogp, llse, _ = spo.spo_pg_loss_fwd(ldesc)
+            dl = spo.spo_pg_loss_bwd(ldesc, llogp, llse, 1.0)
+        torch.cuda.synchronize()
+        spo.spo_kernel_timing_enable(False)
+        lt = spo.spo_kernel_timing_read()
+        fwd_ms = lt["logits_fwd"][0] / reps
+        bwd_ms = lt["logits_bwd"][0] / reps
+        fwd_gbps = Tl * V * 2 / (fwd_ms * 1e-3) / 1e9
+        bwd_gbps = Tl * V * 4 / (bwd_ms * 1e-3) / 1e9
+        out["logits_in"] = {"tokens": Tl, "bytes_per_token_fwd": V * 2, "bytes_per_token_bwd": V * 4,
+                            "fwd_ms": round(fwd_ms, 3), "bwd_ms": round(bwd_ms, 3),
+                            "fwd_GBps": round(fwd_gbps, 1), "bwd_GBps": round(bwd_gbps, 1),
+                            "fwd_frac_hbm": round(fwd_gbps / PEAK_HBM_GBPS, 4),
+                            "bwd_frac_hbm": round(bwd_gbps / PEAK_HBM_GBPS, 4),
+                            "tokens_per_s_fwd_bwd": round(Tl / ((fwd_ms + bwd_ms) * 1e-3), 1)}
+        del logits, dl
+
+    # ---------------------------------------------------------------- the oracle on the host cores
+    if not args.no_cpu_baseline:
+        import oracle
+        n = min(args.cpu_tokens, T)
+        h64 = tb.hidden[:n].double().cpu().numpy()
+        w64 = tb.W.double().cpu().numpy()
+        tg, ol = tb.target[:n], old_logp[:n].double().cpu().numpy()
+        ccu = np.array([0, n], np.int32)
+        t0c = time.perf_counter()
+        eidx = oracle.sample_prompts(a0, b0, B, cfg.eps_explore, cfg.sample_seed, 0)
+        _, eadv, _ = oracle.advantages(a0, b0, eidx, reward.cpu().numpy())
+        oracle.tracker_update(a0, b0, eidx, reward.cpu().numpy(), kl.cpu().numpy(), cfg.d_half, cfg.rho_min, cfg.rho_max)
+        oracle.pg_loss_fwd(h64, w64, tg, ol, None, eadv[:1], ccu, cfg.eps_low, cfg.eps_high)
+        oracle.pg_loss_bwd(h64, w64, tg, ol, None, eadv[:1], ccu, cfg.eps_low, cfg.eps_high)
+        dtc = time.perf_counter() - t0c
+        out["cpu_baseline"] = {"value": round(n / dtc, 3), "unit": "tokens/s", "cores": oracle.num_threads(),
+                               "kind": "oracle",
+                               "sample": f"whole path on the first {n} tokens of the workload as one response, "
+                                         f"full H={H} and V={V} (fp64, {dtc:.1f} s)"}
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

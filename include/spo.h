@@ -11,8 +11,9 @@
  *   - Scalars are host values.  Argument errors are detected on the host
  *     before anything is launched: the call returns a negative status and
  *     leaves all outputs untouched.  0 is success.
- *   - No global state.  Calls that share output or workspace memory must be
- *     ordered by the caller (same stream or events).
+ *   - No global state (the optional kernel timing at the end of this file
+ *     aside).  Calls that share output or workspace memory must be ordered by
+ *     the caller (same stream or events).
  *
  * One training iteration calls, in this order (training-loop algorithm of the
  * paper): spo_sample_prompts -> [rollout, outside this library] ->
@@ -202,6 +203,20 @@ int spo_pg_loss_bwd(const spo_pg_desc *d, const float *logp, const float *lse, f
                     void *d_hidden, int d_hidden_dtype, void *d_W, int d_W_dtype,
                     int accumulate_dW, void *d_logits, int64_t chunk_tokens, void *ws,
                     size_t ws_bytes, spo_stream_t stream);
+
+/* ---------------------------------------------------------------------------
+ * Per-kernel timing (measurement aid, not part of the method; the only state
+ * the library keeps).  While enabled, the loss entry points bracket each launch
+ * of their heavy kernels with a pair of HIP events on the launch stream.
+ * spo_kernel_timing_read waits for the recorded events, writes the summed
+ * milliseconds and the number of launches per kernel class, and forgets them.
+ * Classes: 0 fused forward vocabulary sweep, 1 backward logits recompute,
+ * 2 backward dHidden contraction, 3 backward dW contraction, 4 logits-in forward
+ * pass, 5 logits-in backward pass.  ms and launches are HOST arrays of 6.
+ * ------------------------------------------------------------------------- */
+#define SPO_TIMING_CLASSES 6
+int spo_kernel_timing_enable(int enable);
+int spo_kernel_timing_read(float *ms, int32_t *launches);
 
 #ifdef __cplusplus
 }

@@ -22,7 +22,9 @@ EXPORTS = (
     "spo_advantages", "spo_tracker_update", "spo_tracker_init",
     "spo_pg_loss_fwd_workspace_bytes", "spo_pg_loss_fwd",
     "spo_pg_loss_bwd_workspace_bytes", "spo_pg_loss_bwd",
+    "spo_kernel_timing_enable", "spo_kernel_timing_read",
 )
+TIMING_CLASSES = ("fwd_sweep", "bwd_recompute", "bwd_dhidden", "bwd_dw", "logits_fwd", "logits_bwd")
 
 
 class SpoError(RuntimeError):
@@ -77,6 +79,10 @@ def lib():
         L.spo_pg_loss_bwd.restype = C.c_int
         L.spo_pg_loss_bwd.argtypes = [C.POINTER(PgDesc), vp, vp, f32, vp, C.c_int, vp, C.c_int, C.c_int,
                                       vp, i64, vp, sz, vp]
+        L.spo_kernel_timing_enable.restype = C.c_int
+        L.spo_kernel_timing_enable.argtypes = [C.c_int]
+        L.spo_kernel_timing_read.restype = C.c_int
+        L.spo_kernel_timing_read.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_int32)]
         _lib = L
     return _lib
 
@@ -117,6 +123,19 @@ def _workspace(nbytes: int, device, given=None):
 
 def _dt(t):
     return {torch.float32: SPO_FP32, torch.bfloat16: SPO_BF16}[t]
+
+
+def spo_kernel_timing_enable(enable: bool):
+    _check(lib().spo_kernel_timing_enable(int(bool(enable))), "spo_kernel_timing_enable")
+
+
+def spo_kernel_timing_read():
+    """{class name: (milliseconds, launches)} since the last read."""
+    n = len(TIMING_CLASSES)
+    ms = (C.c_float * n)()
+    cnt = (C.c_int32 * n)()
+    _check(lib().spo_kernel_timing_read(ms, cnt), "spo_kernel_timing_read")
+    return {TIMING_CLASSES[i]: (float(ms[i]), int(cnt[i])) for i in range(n)}
 
 
 # ------------------------------------------------------------------ sampler

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libspo_hip.so")
-SOURCES = ["tracker_adv.hip", "sampler.hip", "pg_logits.hip", "pg_fused.hip", "pg_api.hip"]
+SOURCES = ["tracker_adv.hip", "sampler.hip", "pg_logits.hip", "pg_fused.hip", "pg_api.hip", "timing.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE, "-I" + CSRC,
          # packed fp32 instructions are kept out of the device code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -17,6 +17,7 @@
 
 #include "gemm_core.hpp"
 #include "pg_common.hpp"
+#include "timing.hpp"
 
 namespace spo {
 
@@ -376,6 +377,7 @@ int fused_fwd(const spo_pg_desc *d, float *loss, float *logp, float *lse, float 
             }
         }
         const int64_t blocks = ceil_div(p.nTt, 8) * 8 * p.nsplit;
+        ScopedKernelTimer timer(kTimeFwdSweep, s);
         fwd_sweep_kernel<<<static_cast<unsigned>(blocks), TL::NT, TL::LDS_BYTES, s>>>(
             W, p.Kc * 2, d->V, X, p.Kc * 2, d->T, static_cast<int>(p.Kc / kBK), d->target, p.nsplit, p.nTt, p.nVt,
             p.T_pad, p.part_max, p.part_sum, p.z_target);
@@ -497,16 +499,21 @@ int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float g
             if (d_W) launch_transpose(xs, Tv, H, H, p.XT, Tcp, H, p.Tc, s);
         }
         const TileOrder ord(nVt, Tcp / TL::BN);
+        {
+        ScopedKernelTimer timer(kTimeRecompute, s);
         recompute_dz_kernel<<<static_cast<unsigned>(ord.blocks()), TL::NT, TL::LDS_BYTES, s>>>(
             reinterpret_cast<const char *>(Wk), p.Kc * 2, V, p.V_pad, reinterpret_cast<const char *>(Xk), p.Kc * 2, Tv,
             static_cast<int>(p.Kc / kBK), d->target + t0, lse + t0, p.g + t0, nVt, Tcp / TL::BN,
             d_hidden ? p.dZ : nullptr, p.V_pad, d_W ? p.dZT : nullptr, p.Tc);
+        }
         if (d_hidden) {
+            ScopedKernelTimer timer(kTimeDHidden, s);
             char *dx = static_cast<char *>(d_hidden) + t0 * H * (d_hidden_dtype == SPO_FP32 ? 4 : 2);
             launch_gemm(p.dZ, p.V_pad, Tv, p.WT, p.V_pad, H, p.V_pad, dx, H, d_hidden_dtype, 0, s);
         }
         if (d_W) {
             const int acc = (c > 0 || accumulate_dW) ? 1 : 0;
+            ScopedKernelTimer timer(kTimeDW, s);
             if (d->w_layout == SPO_W_VH)
                 launch_gemm(p.dZT, p.Tc, V, p.XT, p.Tc, H, Tcp, dW32, H, SPO_FP32, acc, s);
             else

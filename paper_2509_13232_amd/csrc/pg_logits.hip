@@ -4,6 +4,7 @@
 #include <algorithm>
 
 #include "pg_common.hpp"
+#include "timing.hpp"
 
 namespace spo {
 
@@ -162,6 +163,7 @@ int logits_fwd(const spo_pg_desc *d, float *loss, float *logp, float *lse, float
     if (ws_bytes < p.bytes) return SPO_EWORKSPACE;
     if (d->T > 0) {
         const unsigned rows = static_cast<unsigned>(d->T);
+        ScopedKernelTimer timer(kTimeLogitsFwd, s);
         if (d->dtype == SPO_BF16) {
             const bf16_t *lg = static_cast<const bf16_t *>(d->logits);
             if (vector_ok<bf16_t>(lg, d->V))
@@ -214,6 +216,7 @@ int logits_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float 
         logp, d->old_logp, d->mask, d->adv_norm, d->cu_seqlens, d->B, d->T, d->T, d->eps_low, d->eps_high, grad_loss,
         p.count, p.g);
     const unsigned rows = static_cast<unsigned>(d->T);
+    ScopedKernelTimer timer(kTimeLogitsBwd, s);
     if (d->dtype == SPO_BF16) {
         const bf16_t *lg = static_cast<const bf16_t *>(d->logits);
         bf16_t *dl = static_cast<bf16_t *>(d_logits);
