@@ -1,0 +1,140 @@
+"""Parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+The oracle cannot evaluate 10^5..10^6 tokens over 151936 vocabulary entries, so:
+  * lse, logp and dHidden rows are compared on sampled tokens (each evaluated by
+    the oracle over the full vocabulary);
+  * dW is compared on sampled vocabulary rows in a second run whose loss mask
+    keeps only a few hundred tokens: the kernels still sweep every token, but the
+    gradient is then fully determined by tokens the oracle can evaluate;
+  * properties that hold at any size: the scalar loss equals an fp64 reduction of
+    the kernel's own per-token values, dW sums to zero over the vocabulary, rows of
+    masked tokens are zero.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2509_13232_amd import workloads as wl
+from pg_cases import f64, rel_l2, say
+
+pytestmark = pytest.mark.gpu
+GRAD_TOL = 1e-2
+
+
+@pytest.fixture(scope="module")
+def spo():
+    from paper_2509_13232_amd import binding
+    binding.lib()
+    assert torch.cuda.is_available()
+    return binding
+
+
+def _sub_problem(tb, W64, rows, adv, seq, old):
+    """Oracle inputs in which every sampled token is a response of its own."""
+    n = len(rows)
+    h = tb.hidden[torch.as_tensor(rows, device=tb.hidden.device)].double().cpu().numpy()
+    return (h, W64, tb.target[rows], old[rows].astype(np.float64), None, adv[seq[rows]].astype(np.float64),
+            np.arange(n + 1, dtype=np.int32))
+
+
+def _run_full(spo, oracle, name, n_rows, n_dw_tokens, n_vsel):
+    cfg = wl.CONFIGS[name]
+    say(f"full-size {name}: generating inputs")
+    tb = wl.token_batch(cfg, device="cuda")
+    T, H, V, B = tb.T, cfg.H, cfg.V, cfg.B
+    rng = np.random.default_rng([wl.MASTER_SEED, 7])
+    adv = rng.standard_normal(B)
+    adv = ((adv - adv.mean()) / adv.std()).astype(np.float32)
+    seq = np.searchsorted(tb.cu_seqlens, np.arange(T), side="right") - 1
+    old_t = wl.behaviour_logp_standin(tb.hidden, tb.W, tb.target, cfg.w_std, tb.noise)
+    old = old_t.cpu().numpy()
+    dev = lambda x, dt: torch.as_tensor(x).to("cuda", dt).contiguous()
+    target, cu, advg = dev(tb.target, torch.int32), dev(tb.cu_seqlens, torch.int32), dev(adv, torch.float32)
+    mask = None if tb.mask is None else dev(tb.mask, torch.uint8)
+    M = T if tb.mask is None else int(tb.mask.sum())
+    W64 = tb.W.double().cpu().numpy()
+
+    # ---------------------------------------------------------------- run 1: the benchmark configuration
+    say(f"full-size {name}: T={T} H={H} V={V} forward+backward")
+    desc = spo.make_desc(tb.hidden, tb.W, target, old_t, mask, advg, cu, cfg.eps_low, cfg.eps_high)
+    loss, logp, lse, stats = spo.spo_pg_loss_fwd(desc)
+    dx, dw = spo.spo_pg_loss_bwd(desc, logp, lse, 1.0)
+    torch.cuda.synchronize()
+    special = [0, 255, 256, T - 1, T - 2, (T // 256) * 256 - 1, min(T - 1, (T // 256) * 256)]
+    rows = np.unique(np.concatenate([rng.choice(T, n_rows, replace=False), special])).astype(np.int64)
+    say(f"full-size {name}: oracle on {len(rows)} sampled tokens")
+    sub = _sub_problem(tb, W64, rows, adv, seq, old)
+    ref = oracle.pg_loss_fwd(*sub, cfg.eps_low, cfg.eps_high)
+    rg = torch.as_tensor(rows, device="cuda")
+    np.testing.assert_allclose(f64(lse[rg]), ref["lse"], atol=2e-4, rtol=0)
+    np.testing.assert_allclose(f64(logp[rg]), ref["logp"], atol=2e-4, rtol=0)
+    # gradient rows: the sub-problem normalises by its own token count, the kernel by M
+    rb = oracle.pg_loss_bwd(*sub, cfg.eps_low, cfg.eps_high, grad_loss=len(rows) / M, want_dw=False)
+    keep = np.ones(len(rows), bool)
+    lo, hi = 1 - cfg.eps_low, 1 + cfg.eps_high
+    keep &= ~((np.abs(ref["ratio"] - lo) < 2e-3 * lo) | (np.abs(ref["ratio"] - hi) < 2e-3 * hi))
+    unmasked = np.ones(len(rows), bool) if tb.mask is None else tb.mask[rows].astype(bool)
+    got = f64(dx[rg])
+    want = rb["d_hidden"] * unmasked[:, None]
+    assert keep.sum() > 0.9 * len(rows)
+    assert rel_l2(got[keep], want[keep]) < GRAD_TOL
+    assert np.abs(got[keep & ~unmasked]).max(initial=0.0) == 0.0
+    per_row = np.linalg.norm(got[keep & unmasked] - want[keep & unmasked], axis=1)
+    scale = np.linalg.norm(want[keep & unmasked], axis=1)
+    active = scale > 0
+    assert (per_row[active] <= 2 * GRAD_TOL * scale[active]).all()          # no single bad row hides in the norm
+    assert (per_row[~active] == 0).all()                                     # clipped tokens: exactly zero rows
+    # loss: equals the fp64 reduction of the kernel's own per-token log-probs
+    lp = f64(logp)
+    ratio = np.exp(lp - old.astype(np.float64))
+    a = adv.astype(np.float64)[seq]
+    obj = np.minimum(ratio * a, np.clip(ratio, lo, hi) * a)
+    m = np.ones(T) if tb.mask is None else tb.mask.astype(np.float64)
+    want_loss = -(m * obj).sum() / m.sum()
+    assert abs(loss.item() - want_loss) <= 2e-3 * abs(want_loss) + 1e-7
+    assert stats[0].item() == M
+    # softmax rows sum to one: dW sums to zero over the vocabulary (per hidden unit)
+    col = dw.sum(dim=0).abs().max().item()
+    assert col <= 1e-2 * dw.abs().sum(dim=0).max().item()
+    del dx, dw
+
+    # ---------------------------------------------------------------- run 2: sparse mask, dW on sampled rows
+    say(f"full-size {name}: sparse-mask run for dW ({n_dw_tokens} live tokens, {n_vsel} vocabulary rows)")
+    live = np.unique(np.concatenate([rng.choice(T, n_dw_tokens, replace=False), [0, T - 1]])).astype(np.int64)
+    # tokens whose ratio sits on a clip bound (fp32 and fp64 may take different branches) stay masked
+    cand = oracle.pg_loss_fwd(*_sub_problem(tb, W64, live, adv, seq, old), cfg.eps_low, cfg.eps_high)["ratio"]
+    live = live[~((np.abs(cand - lo) < 2e-3 * lo) | (np.abs(cand - hi) < 2e-3 * hi))]
+    m2 = np.zeros(T, np.uint8)
+    m2[live] = 1
+    desc2 = spo.make_desc(tb.hidden, tb.W, target, old_t, dev(m2, torch.uint8), advg, cu, cfg.eps_low, cfg.eps_high)
+    loss2, logp2, lse2, _ = spo.spo_pg_loss_fwd(desc2)
+    _, dw2 = spo.spo_pg_loss_bwd(desc2, logp2, lse2, 1.0, want_d_hidden=False)
+    torch.cuda.synchronize()
+    sub2 = _sub_problem(tb, W64, live, adv, seq, old)
+    vsel = np.unique(np.concatenate([rng.choice(V, n_vsel, replace=False), tb.target[live[:8]],
+                                     [0, V - 1, (V // 256) * 256, 255, 256]])).astype(np.int64)
+    rb2 = oracle.pg_loss_bwd(*sub2, cfg.eps_low, cfg.eps_high, vsel=vsel, want_dx=False)
+    rf2 = oracle.pg_loss_fwd(*sub2, cfg.eps_low, cfg.eps_high)
+    near = (np.abs(rf2["ratio"] - lo) < 2e-3 * lo) | (np.abs(rf2["ratio"] - hi) < 2e-3 * hi)
+    assert not near.any(), "a live token sits on a clip bound; change the seed of the live set"
+    assert abs(loss2.item() - rf2["loss"]) <= 2e-3 * abs(rf2["loss"]) + 1e-7
+    got2 = f64(dw2[torch.as_tensor(vsel, device="cuda")])
+    assert rel_l2(got2, rb2["d_W"]) < GRAD_TOL
+    hit = np.isin(vsel, tb.target[live])          # rows that carry a target term vs pure softmax rows
+    assert hit.any() and (~hit).any()
+    assert rel_l2(got2[~hit], rb2["d_W"][~hit]) < 2 * GRAD_TOL
+
+
+@pytest.mark.timeout(600)
+def test_small_model_shape_c2(spo, oracle):
+    _run_full(spo, oracle, "C2", n_rows=96, n_dw_tokens=160, n_vsel=48)
+
+
+@pytest.mark.timeout(900)
+def test_qwen3_8b_head_shape_c3(spo, oracle):
+    _run_full(spo, oracle, "C3", n_rows=96, n_dw_tokens=160, n_vsel=48)
+
+
+@pytest.mark.timeout(900)
+def test_long_horizon_masked_shape_c4(spo, oracle):
+    _run_full(spo, oracle, "C4", n_rows=64, n_dw_tokens=96, n_vsel=32)
