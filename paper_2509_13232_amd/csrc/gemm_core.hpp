@@ -5,7 +5,8 @@
 // contractions of the loss (logits = W h, dHidden = dZ W, dW = dZ^T X) are
 // brought to this form by the callers, so there is one main loop to tune.
 //
-// Data path per K step of 64 elements (128 bytes per operand row):
+// Data path per stage of 64 contraction elements (128 bytes = one cache line per
+// operand row; half-line rows were measured to halve the L2->LDS rate):
 //   HBM/L2 --global_load_lds_dwordx4--> LDS (two stages)  --ds_read_b128-->
 //   VGPR fragments --v_mfma_f32_32x32x16_bf16--> fp32 accumulators.
 // Global loads go straight to LDS without passing through registers.  A tile
@@ -28,10 +29,15 @@ namespace spo {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
-constexpr int kBK = 64;  // contraction elements per stage
+constexpr int kBK = 64;      // contraction elements per stage
+constexpr int kStages = 2;   // LDS stages
+constexpr int kRowBytes = kBK * 2;
+constexpr int kChunks = kRowBytes / 16;
 
-// chunk swizzle of a tile row; a bijection on 0..7 both over rows 0..7 and over
-// the rows of equal parity in 0..15
+// chunk swizzle of a tile row (3 bits): a bijection on 0..7 both over rows 0..7
+// and over the rows of equal parity in 0..15, i.e. 16 consecutive rows reading
+// the same chunk touch 16 different 16-byte slots of any 256-byte window, and 8
+// consecutive rows 8 different slots of any 128-byte window
 __device__ __forceinline__ int swz(int row) {
     return ((row >> 1) & 3) | (((row ^ (row >> 3)) & 1) << 2);
 }
@@ -42,12 +48,14 @@ struct Tile {
     static constexpr int NWAVE = WGM * WGN, NT = NWAVE * kWave;
     static constexpr int WM = BM / WGM, WN = BN / WGN;     // wave tile
     static constexpr int FM = WM / 32, FN = WN / 32;       // 32x32 blocks per wave
-    static constexpr int A_BYTES = BM * kBK * 2, B_BYTES = BN * kBK * 2;
+    static constexpr int KK = kBK / 16;                    // MFMA k-slices per stage
+    static constexpr int A_BYTES = BM * kRowBytes, B_BYTES = BN * kRowBytes;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-    static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
-    static constexpr int A_LOADS = BM * 8 / NT, B_LOADS = BN * 8 / NT;
-    static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile rows must split evenly over the threads");
-    static_assert((NT / 8) % 16 == 0, "swizzle must be the same for every load of a thread");
+    static constexpr int LDS_BYTES = kStages * STAGE_BYTES;
+    static constexpr int A_LOADS = BM * kChunks / NT, B_LOADS = BN * kChunks / NT;
+    static constexpr int STAGE_LOADS = A_LOADS + B_LOADS;  // DMA instructions per thread and stage
+    static_assert(BM * kChunks % NT == 0 && BN * kChunks % NT == 0, "tile rows must split evenly over the threads");
+    static_assert((NT / kChunks) % 16 == 0, "swizzle must be the same for every load of a thread");
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile is made of 32x32 blocks");
 
     typedef f32x16_t Acc[FM][FN];
@@ -67,77 +75,133 @@ struct Tile {
     }
 
     // acc += A[m0.., :K] * B[n0.., :K]^T.  Rows beyond M / N are read from the last
-    // valid row (the caller masks them).  K = 64 * KT.  lds: LDS_BYTES bytes,
+    // valid row (the caller masks them).  K = kBK * KT.  lds: LDS_BYTES bytes,
     // 16-byte aligned.  All threads of the block must call this together.
     __device__ static __forceinline__ void mainloop(const char *__restrict__ A, int64_t lda_bytes, int64_t m0, int64_t M,
                                                     const char *__restrict__ B, int64_t ldb_bytes, int64_t n0, int64_t N,
                                                     int KT, char *lds, Acc &acc) {
         const int tid = threadIdx.x, lane = tid & 63, wave = wave_id();
-        // ---- DMA addressing: slot q = i*NT + tid of a tile <-> (row q/8, position q%8)
-        const int ld_row = tid >> 3;
-        const int ld_chunk = (tid & 7) ^ swz(ld_row & 15);
+        // ---- DMA addressing: slot q = i*NT + tid of a tile <-> (row q/kChunks, position q%kChunks)
+        const int ld_row = tid / kChunks;
+        const int ld_chunk = (tid % kChunks) ^ swz(ld_row & 15);
         // 32-bit byte offsets from the tile's first row (a tile spans < 4 GiB)
-        const char *a_tile = A + m0 * lda_bytes, *b_tile = B + n0 * ldb_bytes;
+        // (the tile origins are the same for every lane; say so, the DMA wants them in SGPRs)
+        auto uniform = [](const char *p) {
+            const uint64_t u = reinterpret_cast<uint64_t>(p);
+            const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(u));
+            const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(u >> 32));
+            return reinterpret_cast<const char *>((static_cast<uint64_t>(hi) << 32) | lo);
+        };
+        const char *a_tile = uniform(A + m0 * lda_bytes), *b_tile = uniform(B + n0 * ldb_bytes);
         uint32_t oa[A_LOADS], ob[B_LOADS];
 #pragma unroll
         for (int i = 0; i < A_LOADS; ++i) {
-            int64_t r = i * (NT / 8) + ld_row;
+            int64_t r = i * (NT / kChunks) + ld_row;
             r = m0 + r < M ? r : M - 1 - m0;
             oa[i] = static_cast<uint32_t>(r * lda_bytes + ld_chunk * 16);
         }
 #pragma unroll
         for (int i = 0; i < B_LOADS; ++i) {
-            int64_t r = i * (NT / 8) + ld_row;
+            int64_t r = i * (NT / kChunks) + ld_row;
             r = n0 + r < N ? r : N - 1 - n0;
             ob[i] = static_cast<uint32_t>(r * ldb_bytes + ld_chunk * 16);
         }
-        auto issue = [&](int stage, int64_t koff) {
-            char *la = lds + stage * STAGE_BYTES + wave * (kWave * 16);
-            char *lb = la + A_BYTES;
-            const char *ak = a_tile + koff, *bk = b_tile + koff;
-#pragma unroll
-            for (int i = 0; i < A_LOADS; ++i)
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void *)(ak + oa[i]),
-                    (__attribute__((address_space(3))) void *)(la + i * (NT * 16)), 16, 0, 0);
-#pragma unroll
-            for (int i = 0; i < B_LOADS; ++i)
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void *)(bk + ob[i]),
-                    (__attribute__((address_space(3))) void *)(lb + i * (NT * 16)), 16, 0, 0);
+        // The DMA is issued from inline assembly.  Issued through the compiler it would
+        // make every later LDS read wait for ALL outstanding DMA (the wait-count pass
+        // cannot tell the stages apart); here every vmcnt wait for these loads is
+        // explicit instead.  M0 holds the LDS base of the 64 lanes x 16 bytes the
+        // instruction writes.
+        const uint32_t lds_base = static_cast<uint32_t>(
+            reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char *)lds));
+        auto dma = [](const char *base, uint32_t off, uint32_t lds_addr) {
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(lds_addr), "v"(off), "s"(base)
+                         : "memory");
         };
+        // DMA instruction i (0 .. STAGE_LOADS-1) of this thread's share of stage kt
+        auto dma_one = [&](int kt, int i) {
+            const uint32_t la = lds_base + (kt % kStages) * STAGE_BYTES + wave * (kWave * 16);
+            const int64_t koff = static_cast<int64_t>(kt) * kRowBytes;
+            if (i < A_LOADS) dma(a_tile + koff, oa[i], la + i * (NT * 16));
+            else dma(b_tile + koff, ob[i - A_LOADS], la + A_BYTES + (i - A_LOADS) * (NT * 16));
+        };
+        auto issue = [&](int kt) {
+#pragma unroll
+            for (int i = 0; i < STAGE_LOADS; ++i) dma_one(kt, i);
+        };
+        auto wait_dma = [] { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
         // ---- fragment addressing: lane reads row (l%32) of a 32-row block, chunk 2*kk + l/32
         const int fr_sw = swz(lane & 15);
-        int fr_off[4];
+        int fr_off[KK];
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) fr_off[kk] = (lane & 31) * 128 + (((2 * kk + (lane >> 5)) ^ fr_sw) * 16);
-        const int a_base = wave_m0() * 128, b_base = A_BYTES + wave_n0() * 128;
+        for (int kk = 0; kk < KK; ++kk) fr_off[kk] = (lane & 31) * kRowBytes + (((2 * kk + (lane >> 5)) ^ fr_sw) * 16);
+        const int a_base = wave_m0() * kRowBytes, b_base = A_BYTES + wave_n0() * kRowBytes;
 
+        // Two groups of four wavefronts (one of each per SIMD) run half a step apart:
+        // while one group multiplies, the other reads its fragments from LDS, so the
+        // MFMA pipe of every SIMD always has a wavefront to serve.  Barrier j of one
+        // group meets barrier j of the other; group 1 passes one extra barrier first
+        // and group 0 one extra at the end.  With I(j) the interval after barrier j,
+        // group 0 reads stage s in I(2s) and multiplies in I(2s+1); group 1 reads in
+        // I(2s+1) and multiplies in I(2s+2).  The buffer of stage s+1 is free from
+        // barrier 2s on and must be complete at barrier 2s+2, so its DMA is issued in
+        // I(2s) and awaited at the end of I(2s+1).  The address unit takes about 16
+        // cycles per DMA instruction and a burst of them blocks the issuing
+        // wavefront: group 1, which multiplies during I(2s), feeds its share one
+        // instruction per two MFMAs, and group 0 issues its share behind its
+        // fragment reads.
+        static_assert(NWAVE == 8, "the main loop is written for two groups of four wavefronts");
+        static_assert(kStages == 2, "the schedule below is for two stages");
+        const int group = wave >> 2;
+        auto fence_barrier = [] {
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+        };
         __syncthreads();  // every wave is done with the previous contents of lds
-        issue(0, 0);
+        issue(0);
+        wait_dma();
+        fence_barrier();
+        if (group == 1) {
+            if (KT > 1) issue(1);
+            fence_barrier();
+        }
         for (int kt = 0; kt < KT; ++kt) {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // my part of stage kt has landed
-            __syncthreads();                                  // ... and everyone else's
-            const char *st = lds + (kt & 1) * STAGE_BYTES;
-            bf16x8_t af[FM][4], bf[FN][4];
+            const char *st = lds + (kt % kStages) * STAGE_BYTES;
+            bf16x8_t af[FM][KK], bf[FN][KK];
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
+            for (int kk = 0; kk < KK; ++kk) {
 #pragma unroll
                 for (int fm = 0; fm < FM; ++fm)
-                    af[fm][kk] = *reinterpret_cast<const bf16x8_t *>(st + a_base + fm * (32 * 128) + fr_off[kk]);
+                    af[fm][kk] = *reinterpret_cast<const bf16x8_t *>(st + a_base + fm * (32 * kRowBytes) + fr_off[kk]);
 #pragma unroll
                 for (int fn = 0; fn < FN; ++fn)
-                    bf[fn][kk] = *reinterpret_cast<const bf16x8_t *>(st + b_base + fn * (32 * 128) + fr_off[kk]);
+                    bf[fn][kk] = *reinterpret_cast<const bf16x8_t *>(st + b_base + fn * (32 * kRowBytes) + fr_off[kk]);
             }
-            if (kt + 1 < KT) issue((kt + 1) & 1, static_cast<int64_t>(kt + 1) * (kBK * 2));
+            if (group == 0) {
+                if (kt + 1 < KT) issue(kt + 1);
+            } else {
+                wait_dma();  // my share of stage kt+1, issued during the previous multiply phase
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // fragments are in registers
+            fence_barrier();
+            __builtin_amdgcn_s_setprio(1);
+            const bool feed = group == 1 && kt + 2 < KT;  // wave-uniform
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-                for (int fm = 0; fm < FM; ++fm)
-#pragma unroll
-                    for (int fn = 0; fn < FN; ++fn)
-                        acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[fm][kk], bf[fn][kk], acc[fm][fn], 0, 0, 0);
+            for (int j = 0; j < KK * FM * FN; ++j) {
+                const int kk = j / (FM * FN), fm = (j / FN) % FM, fn = j % FN;
+                if (j % 2 == 0 && j / 2 < STAGE_LOADS) {
+                    if (feed) dma_one(kt + 2, j / 2);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[fm][kk], bf[fn][kk], acc[fm][fn], 0, 0, 0);
+            }
+            __builtin_amdgcn_s_setprio(0);
+            if (group == 0) wait_dma();  // my share of stage kt+1
+            fence_barrier();
         }
+        if (group == 0) fence_barrier();
     }
 
     __device__ static __forceinline__ void zero(Acc &acc) {
