@@ -211,13 +211,28 @@ recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, in
     TL::Acc acc;
     TL::zero(acc);
     TL::mainloop(W, ldw_bytes, m0, V, X, ldx_bytes, n0, T_valid, KT, lds, acc);
+    if (m0 + TL::BM > V) {  // ragged last tile: rows past the vocabulary get probability zero
+#pragma unroll
+        for (int fm = 0; fm < TL::FM; ++fm)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (m0 + TL::acc_row(fm, r) >= V)
+#pragma unroll
+                    for (int fn = 0; fn < TL::FN; ++fn) acc[fm][fn][r] = kNegBig;
+    }
+    const int quad_lane = threadIdx.x & 3;
 #pragma unroll
     for (int fn = 0; fn < TL::FN; ++fn) {
         const int64_t t = n0 + TL::acc_col(fn);
         const bool tok_ok = t < T_valid;
         const float gt = tok_ok ? g[t] : 0.0f;
-        const float nl = tok_ok ? -lse[t] * kLog2e : 0.0f;
-        const int32_t y = tok_ok ? target[t] : -1;
+        const float ngt = -gt;
+        // padded tokens: scale zero and an exponent that underflows, so that 0 * p stays 0
+        const float nl = tok_ok ? -lse[t] * kLog2e : kNegBig;
+        // distance of the target's vocabulary row from this wave's first row
+        const int dy = (tok_ok ? target[t] : -1) - static_cast<int>(m0 + TL::wave_m0());
+        const bool mine = static_cast<unsigned>(dy) < static_cast<unsigned>(TL::WM) && ((dy >> 2) & 1) == ((threadIdx.x & 63) >> 5);
+        const int fq = dy >> 5, rq = ((dy & 31) >> 3) * 4 + (dy & 3);
 #pragma unroll
         for (int fm = 0; fm < TL::FM; ++fm) {
 #pragma unroll
@@ -225,22 +240,42 @@ recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, in
                 const int64_t v0 = m0 + TL::acc_row(fm, r4 * 4);
                 float dz[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int64_t v = v0 + i;
-                    const float p = __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r4 * 4 + i], kLog2e, nl));
-                    float x = (v == y ? gt : 0.0f) - gt * p;
-                    dz[i] = (gt != 0.0f && v < V) ? x : 0.0f;
+                for (int i = 0; i < 4; ++i)
+                    dz[i] = ngt * __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r4 * 4 + i], kLog2e, nl));
+                if (mine && fm == fq && (rq >> 2) == r4) {  // the one-hot term
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if ((rq & 3) == i) dz[i] += gt;
                 }
+                const uint32_t x = pack_bf16x2_rn(dz[0], dz[1]), y = pack_bf16x2_rn(dz[2], dz[3]);
                 if (dZ && v0 < V_pad) {
                     uint2 pk;
-                    pk.x = pack_bf16x2(dz[0], dz[1]);
-                    pk.y = pack_bf16x2(dz[2], dz[3]);
+                    pk.x = x;
+                    pk.y = y;
                     *reinterpret_cast<uint2 *>(dZ + t * ldz + v0) = pk;
                 }
                 if (dZT) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if (v0 + i < V) dZT[(v0 + i) * ldzt + t] = f32_to_bf16(dz[i]);
+                    // The four lanes of a quad hold four consecutive tokens of the same four
+                    // vocabulary rows: transpose that 4x4 block in registers so that lane j
+                    // of the quad holds row v0+j for the quad's four tokens (8 bytes, one store).
+                    const int j = quad_lane;
+                    // step 1: 2x2 blocks of 16-bit values between lanes j and j^1
+                    const uint32_t xn = __builtin_amdgcn_mov_dpp(x, 0xB1, 0xF, 0xF, true);  // quad_perm [1,0,3,2]
+                    const uint32_t yn = __builtin_amdgcn_mov_dpp(y, 0xB1, 0xF, 0xF, true);
+                    // even lane: (own low, neighbour low); odd lane: (neighbour high, own high)
+                    // (v_perm_b32: selector bytes 0-3 pick from the second operand, 4-7 from the first)
+                    const uint32_t sel = (j & 1) ? 0x03020706u : 0x05040100u;
+                    const uint32_t x1 = __builtin_amdgcn_perm(xn, x, sel);
+                    const uint32_t y1 = __builtin_amdgcn_perm(yn, y, sel);
+                    // now x1 = row (j&1) of tokens pair (j>>1), y1 = row 2+(j&1) of the same pair
+                    // step 2: 32-bit exchange between lanes j and j^2
+                    const uint32_t give = (j & 2) ? x1 : y1;
+                    const uint32_t got = __builtin_amdgcn_mov_dpp(give, 0x4E, 0xF, 0xF, true);  // quad_perm [2,3,0,1]
+                    uint2 row;
+                    row.x = (j & 2) ? got : x1;
+                    row.y = (j & 2) ? y1 : got;
+                    const int64_t vr = v0 + j, tq = t - j;
+                    if (vr < V) *reinterpret_cast<uint2 *>(dZT + vr * ldzt + tq) = row;
                 }
             }
         }
@@ -390,7 +425,7 @@ int fused_fwd(const spo_pg_desc *d, float *loss, float *logp, float *lse, float 
 }
 
 struct BwdPlan {
-    int64_t Tc, V_pad, Kc, T_pad;
+    int64_t Tc, ldt, V_pad, Kc, T_pad;  // ldt: row stride of the token-contiguous scratch (dZT, XT)
     double *count;
     float *g, *dW_acc;
     bf16_t *WT, *XT, *dZ, *dZT, *Xs, *Ws, *Wvh;
@@ -402,6 +437,7 @@ static BwdPlan plan_bwd(const spo_pg_desc *d, int64_t chunk_tokens, void *ws, bo
     const int64_t Tmax = round_up(std::max<int64_t>(d->T, 1), TL::BN);
     int64_t tc = chunk_tokens > 0 ? chunk_tokens : kDefaultChunk;
     p.Tc = std::min(round_up(tc, TL::BN), Tmax);
+    p.ldt = p.Tc + 64;  // keeps the rows of a tile off a common power-of-two stride
     p.T_pad = Tmax;
     p.V_pad = round_up(d->V, kBK);
     p.Kc = d->dtype == SPO_FP32 ? kSplitTerms * d->H : d->H;
@@ -409,9 +445,9 @@ static BwdPlan plan_bwd(const spo_pg_desc *d, int64_t chunk_tokens, void *ws, bo
     p.count = a.take<double>(1);
     p.g = a.take<float>(p.T_pad);
     p.WT = a.take<bf16_t>(static_cast<size_t>(d->H) * p.V_pad);
-    p.XT = a.take<bf16_t>(static_cast<size_t>(d->H) * p.Tc);
+    p.XT = a.take<bf16_t>(static_cast<size_t>(d->H) * p.ldt);
     p.dZ = a.take<bf16_t>(static_cast<size_t>(p.Tc) * p.V_pad);
-    p.dZT = a.take<bf16_t>(static_cast<size_t>(d->V) * p.Tc);
+    p.dZT = a.take<bf16_t>(static_cast<size_t>(d->V) * p.ldt);
     p.Xs = p.Ws = p.Wvh = nullptr;
     p.dW_acc = nullptr;
     if (d->dtype == SPO_FP32) {
@@ -492,19 +528,19 @@ int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float g
             const float *xs = static_cast<const float *>(d->hidden) + t0 * H;
             split_expand_kernel<<<grid1(Tv * H), 256, 0, s>>>(xs, Tv, H, p.Xs, 1);
             Xk = p.Xs;
-            if (d_W) launch_transpose(xs, Tv, H, H, p.XT, Tcp, H, p.Tc, s);
+            if (d_W) launch_transpose(xs, Tv, H, H, p.XT, Tcp, H, p.ldt, s);
         } else {
             const bf16_t *xs = static_cast<const bf16_t *>(d->hidden) + t0 * H;
             Xk = xs;
-            if (d_W) launch_transpose(xs, Tv, H, H, p.XT, Tcp, H, p.Tc, s);
+            if (d_W) launch_transpose(xs, Tv, H, H, p.XT, Tcp, H, p.ldt, s);
         }
-        const TileOrder ord(nVt, Tcp / TL::BN);
         {
-        ScopedKernelTimer timer(kTimeRecompute, s);
-        recompute_dz_kernel<<<static_cast<unsigned>(ord.blocks()), TL::NT, TL::LDS_BYTES, s>>>(
-            reinterpret_cast<const char *>(Wk), p.Kc * 2, V, p.V_pad, reinterpret_cast<const char *>(Xk), p.Kc * 2, Tv,
-            static_cast<int>(p.Kc / kBK), d->target + t0, lse + t0, p.g + t0, nVt, Tcp / TL::BN,
-            d_hidden ? p.dZ : nullptr, p.V_pad, d_W ? p.dZT : nullptr, p.Tc);
+            const TileOrder ord(nVt, Tcp / TL::BN);
+            ScopedKernelTimer timer(kTimeRecompute, s);
+            recompute_dz_kernel<<<static_cast<unsigned>(ord.blocks()), TL::NT, TL::LDS_BYTES, s>>>(
+                reinterpret_cast<const char *>(Wk), p.Kc * 2, V, p.V_pad, reinterpret_cast<const char *>(Xk), p.Kc * 2,
+                Tv, static_cast<int>(p.Kc / kBK), d->target + t0, lse + t0, p.g + t0, nVt, Tcp / TL::BN,
+                d_hidden ? p.dZ : nullptr, p.V_pad, d_W ? p.dZT : nullptr, p.ldt);
         }
         if (d_hidden) {
             ScopedKernelTimer timer(kTimeDHidden, s);
@@ -515,9 +551,9 @@ int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float g
             const int acc = (c > 0 || accumulate_dW) ? 1 : 0;
             ScopedKernelTimer timer(kTimeDW, s);
             if (d->w_layout == SPO_W_VH)
-                launch_gemm(p.dZT, p.Tc, V, p.XT, p.Tc, H, Tcp, dW32, H, SPO_FP32, acc, s);
+                launch_gemm(p.dZT, p.ldt, V, p.XT, p.ldt, H, Tcp, dW32, H, SPO_FP32, acc, s);
             else
-                launch_gemm(p.XT, p.Tc, H, p.dZT, p.Tc, V, Tcp, dW32, V, SPO_FP32, acc, s);
+                launch_gemm(p.XT, p.ldt, H, p.dZT, p.ldt, V, Tcp, dW32, V, SPO_FP32, acc, s);
         }
     }
     if (need_acc) f32_to_bf16_kernel<<<grid1(V * H), 256, 0, s>>>(p.dW_acc, static_cast<bf16_t *>(d_W), V * H);
