@@ -74,62 +74,85 @@ struct Tile {
         return wave_n0() + fn * 32 + (threadIdx.x & 31);
     }
 
+    // Global -> LDS transfers of one tile: addressing and issue.
+    // Slot q = i*NT + tid of a tile <-> (row q/kChunks, position q%kChunks).
+    struct Dma {
+        const char *a_tile, *b_tile;     // first row of the A / B panel (wave-uniform)
+        uint32_t oa[A_LOADS], ob[B_LOADS];  // this lane's byte offsets inside the panels
+        uint32_t lds_wave;               // LDS address of this wave's 1 KiB slice of stage 0
+
+        __device__ __forceinline__ Dma(const char *A, int64_t lda_bytes, int64_t m0, int64_t M, const char *B,
+                                       int64_t ldb_bytes, int64_t n0, int64_t N, char *lds) {
+            const int tid = threadIdx.x;
+            const int ld_row = tid / kChunks;
+            const int ld_chunk = (tid % kChunks) ^ swz(ld_row & 15);
+            // the tile origins are the same for every lane; say so, the DMA wants them in SGPRs
+            auto uniform = [](const char *p) {
+                const uint64_t u = reinterpret_cast<uint64_t>(p);
+                const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(u));
+                const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(u >> 32));
+                return reinterpret_cast<const char *>((static_cast<uint64_t>(hi) << 32) | lo);
+            };
+            a_tile = uniform(A + m0 * lda_bytes);
+            b_tile = uniform(B + n0 * ldb_bytes);
+            // 32-bit byte offsets from the tile's first row (a tile spans < 4 GiB)
+#pragma unroll
+            for (int i = 0; i < A_LOADS; ++i) {
+                int64_t r = i * (NT / kChunks) + ld_row;
+                r = m0 + r < M ? r : M - 1 - m0;
+                oa[i] = static_cast<uint32_t>(r * lda_bytes + ld_chunk * 16);
+            }
+#pragma unroll
+            for (int i = 0; i < B_LOADS; ++i) {
+                int64_t r = i * (NT / kChunks) + ld_row;
+                r = n0 + r < N ? r : N - 1 - n0;
+                ob[i] = static_cast<uint32_t>(r * ldb_bytes + ld_chunk * 16);
+            }
+            lds_wave = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char *)lds)) +
+                       wave_id() * (kWave * 16);
+        }
+        // The DMA is issued from inline assembly.  Issued through the compiler it would
+        // make every later LDS read wait for ALL outstanding DMA (the wait-count pass
+        // cannot tell the stages apart); here every vmcnt wait for these loads is
+        // explicit instead.  M0 holds the LDS base of the 64 lanes x 16 bytes written.
+        __device__ static __forceinline__ void dma(const char *base, uint32_t off, uint32_t lds_addr) {
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(lds_addr), "v"(off), "s"(base)
+                         : "memory");
+        }
+        // DMA instruction i (0 .. STAGE_LOADS-1) of this thread's share of stage kt
+        __device__ __forceinline__ void one(int kt, int i) const {
+            const uint32_t la = lds_wave + (kt % kStages) * STAGE_BYTES;
+            const int64_t koff = static_cast<int64_t>(kt) * kRowBytes;
+            if (i < A_LOADS) dma(a_tile + koff, oa[i], la + i * (NT * 16));
+            else dma(b_tile + koff, ob[i - A_LOADS], la + A_BYTES + (i - A_LOADS) * (NT * 16));
+        }
+        __device__ __forceinline__ void stage(int kt) const {
+#pragma unroll
+            for (int i = 0; i < STAGE_LOADS; ++i) one(kt, i);
+        }
+    };
+
+    // Starts the transfer of stage 0 of a tile while the caller still works on the
+    // previous tile's accumulators (its epilogue); the matching mainloop call passes
+    // stage0_issued = true.  All threads of the block must call this together.
+    __device__ static __forceinline__ void prefetch(const char *__restrict__ A, int64_t lda_bytes, int64_t m0, int64_t M,
+                                                    const char *__restrict__ B, int64_t ldb_bytes, int64_t n0, int64_t N,
+                                                    char *lds) {
+        const Dma d(A, lda_bytes, m0, M, B, ldb_bytes, n0, N, lds);
+        __syncthreads();  // every wave is done with the previous contents of lds
+        d.stage(0);
+    }
+
     // acc += A[m0.., :K] * B[n0.., :K]^T.  Rows beyond M / N are read from the last
     // valid row (the caller masks them).  K = kBK * KT.  lds: LDS_BYTES bytes,
     // 16-byte aligned.  All threads of the block must call this together.
     __device__ static __forceinline__ void mainloop(const char *__restrict__ A, int64_t lda_bytes, int64_t m0, int64_t M,
                                                     const char *__restrict__ B, int64_t ldb_bytes, int64_t n0, int64_t N,
-                                                    int KT, char *lds, Acc &acc) {
-        const int tid = threadIdx.x, lane = tid & 63, wave = wave_id();
-        // ---- DMA addressing: slot q = i*NT + tid of a tile <-> (row q/kChunks, position q%kChunks)
-        const int ld_row = tid / kChunks;
-        const int ld_chunk = (tid % kChunks) ^ swz(ld_row & 15);
-        // 32-bit byte offsets from the tile's first row (a tile spans < 4 GiB)
-        // (the tile origins are the same for every lane; say so, the DMA wants them in SGPRs)
-        auto uniform = [](const char *p) {
-            const uint64_t u = reinterpret_cast<uint64_t>(p);
-            const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(u));
-            const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(u >> 32));
-            return reinterpret_cast<const char *>((static_cast<uint64_t>(hi) << 32) | lo);
-        };
-        const char *a_tile = uniform(A + m0 * lda_bytes), *b_tile = uniform(B + n0 * ldb_bytes);
-        uint32_t oa[A_LOADS], ob[B_LOADS];
-#pragma unroll
-        for (int i = 0; i < A_LOADS; ++i) {
-            int64_t r = i * (NT / kChunks) + ld_row;
-            r = m0 + r < M ? r : M - 1 - m0;
-            oa[i] = static_cast<uint32_t>(r * lda_bytes + ld_chunk * 16);
-        }
-#pragma unroll
-        for (int i = 0; i < B_LOADS; ++i) {
-            int64_t r = i * (NT / kChunks) + ld_row;
-            r = n0 + r < N ? r : N - 1 - n0;
-            ob[i] = static_cast<uint32_t>(r * ldb_bytes + ld_chunk * 16);
-        }
-        // The DMA is issued from inline assembly.  Issued through the compiler it would
-        // make every later LDS read wait for ALL outstanding DMA (the wait-count pass
-        // cannot tell the stages apart); here every vmcnt wait for these loads is
-        // explicit instead.  M0 holds the LDS base of the 64 lanes x 16 bytes the
-        // instruction writes.
-        const uint32_t lds_base = static_cast<uint32_t>(
-            reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char *)lds));
-        auto dma = [](const char *base, uint32_t off, uint32_t lds_addr) {
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :
-                         : "s"(lds_addr), "v"(off), "s"(base)
-                         : "memory");
-        };
-        // DMA instruction i (0 .. STAGE_LOADS-1) of this thread's share of stage kt
-        auto dma_one = [&](int kt, int i) {
-            const uint32_t la = lds_base + (kt % kStages) * STAGE_BYTES + wave * (kWave * 16);
-            const int64_t koff = static_cast<int64_t>(kt) * kRowBytes;
-            if (i < A_LOADS) dma(a_tile + koff, oa[i], la + i * (NT * 16));
-            else dma(b_tile + koff, ob[i - A_LOADS], la + A_BYTES + (i - A_LOADS) * (NT * 16));
-        };
-        auto issue = [&](int kt) {
-#pragma unroll
-            for (int i = 0; i < STAGE_LOADS; ++i) dma_one(kt, i);
-        };
+                                                    int KT, char *lds, Acc &acc, bool stage0_issued = false) {
+        const int lane = threadIdx.x & 63, wave = wave_id();
+        const Dma d(A, lda_bytes, m0, M, B, ldb_bytes, n0, N, lds);
         auto wait_dma = [] { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
         // ---- fragment addressing: lane reads row (l%32) of a 32-row block, chunk 2*kk + l/32
         const int fr_sw = swz(lane & 15);
@@ -159,12 +182,14 @@ struct Tile {
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
         };
-        __syncthreads();  // every wave is done with the previous contents of lds
-        issue(0);
+        if (!stage0_issued) {
+            __syncthreads();  // every wave is done with the previous contents of lds
+            d.stage(0);
+        }
         wait_dma();
         fence_barrier();
         if (group == 1) {
-            if (KT > 1) issue(1);
+            if (KT > 1) d.stage(1);
             fence_barrier();
         }
         for (int kt = 0; kt < KT; ++kt) {
@@ -180,7 +205,7 @@ struct Tile {
                     bf[fn][kk] = *reinterpret_cast<const bf16x8_t *>(st + b_base + fn * (32 * kRowBytes) + fr_off[kk]);
             }
             if (group == 0) {
-                if (kt + 1 < KT) issue(kt + 1);
+                if (kt + 1 < KT) d.stage(kt + 1);
             } else {
                 wait_dma();  // my share of stage kt+1, issued during the previous multiply phase
             }
@@ -192,7 +217,7 @@ struct Tile {
             for (int j = 0; j < KK * FM * FN; ++j) {
                 const int kk = j / (FM * FN), fm = (j / FN) % FM, fn = j % FN;
                 if (j % 2 == 0 && j / 2 < STAGE_LOADS) {
-                    if (feed) dma_one(kt + 2, j / 2);
+                    if (feed) d.one(kt + 2, j / 2);
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[fm][kk], bf[fn][kk], acc[fm][fn], 0, 0, 0);

@@ -119,7 +119,9 @@ fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const
         const int64_t m0 = vt * TL::BM;
         TL::Acc acc;
         TL::zero(acc);
-        TL::mainloop(W, ldw_bytes, m0, V, X, ldx_bytes, n0, T, KT, lds, acc);
+        TL::mainloop(W, ldw_bytes, m0, V, X, ldx_bytes, n0, T, KT, lds, acc, vt > vt0);
+        // the first stage of the next vocabulary tile travels while this one is reduced
+        if (vt + 1 < vt1) TL::prefetch(W, ldw_bytes, m0 + TL::BM, V, X, ldx_bytes, n0, T, lds);
         if (m0 + TL::BM > V) {  // ragged last tile: rows past the vocabulary do not count
 #pragma unroll
             for (int fm = 0; fm < TL::FM; ++fm)
