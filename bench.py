@@ -24,6 +24,14 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 
+# Bytes that crossed the L2 <-> fabric boundary per launch (reads + writes), from rocprofv3
+# FETCH_SIZE / WRITE_SIZE runs of this script at the default workload and chunk size, each
+# scaled by what the same counter reads for a plain 1 GiB copy (profiles/step_c3_hbm_traffic.md).
+# Valid only for the kernels as profiled: None for any other workload or chunk size.
+TRAFFIC_BYTES_PER_LAUNCH = {
+    ("C3", 0): {"fwd_sweep": None, "bwd_recompute": None, "bwd_dhidden": None, "bwd_dw": None},
+}
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -141,7 +149,8 @@ def main() -> int:
     flops_per_launch = thv * args.steps / n_dom
     achieved = flops_per_launch / (ms_dom / n_dom * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                "traffic": TRAFFIC_BYTES_PER_LAUNCH.get((cfg.name, args.chunk_tokens), {}).get(dom),
                 "flops_per_launch": flops_per_launch, "avg_launch_ms": round(ms_dom / n_dom, 4),
                 "kernels": kern}
 

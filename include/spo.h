@@ -106,6 +106,15 @@ int spo_advantages(const float *alpha, const float *beta, int64_t N, const int32
                    const float *reward, int32_t B, int ddof, float eps_norm, int use_baseline,
                    float *adv_raw, float *adv_norm, float *stats, spo_stream_t stream);
 
+/* Diagnostics of the unnormalised advantages that the paper's analysis tracks
+ * (Experiments, "Signal Efficiency and Information Loss" and "Signal Stability and
+ * Advantage Variance"): diag[0], diag[1] = share of responses with |A| <= tau_tight
+ * and |A| <= tau_loose (the paper uses 1e-4 and 0.02), diag[2] = population
+ * variance of A, diag[3] = population variance of the rewards (the "no baseline"
+ * reference).  adv_raw, reward [B] fp32; diag fp32[4]; tau_tight <= tau_loose. */
+int spo_advantage_diagnostics(const float *adv_raw, const float *reward, int32_t B, float tau_tight,
+                              float tau_loose, float *diag, spo_stream_t stream);
+
 /* ---------------------------------------------------------------------------
  * Tracker update (Method, "A KL-Adaptive Value Tracker"): for every observed
  * response, rho = 2^(-D/D_half) kept inside [rho_min, rho_max],

@@ -60,6 +60,8 @@ def _load():
             lib.spo_oracle_advantages.argtypes = [
                 _d, _d, C.c_int64, _i32, _d, C.c_int32, C.c_int, C.c_double, C.c_int,
                 _d, _d, _d]
+            lib.spo_oracle_advantage_diagnostics.restype = None
+            lib.spo_oracle_advantage_diagnostics.argtypes = [_d, _d, C.c_int32, C.c_double, C.c_double, _d]
             lib.spo_oracle_weights.restype = None
             lib.spo_oracle_weights.argtypes = [_f, _f, C.c_int64, C.c_double, _d]
             lib.spo_oracle_weight_code.restype = C.c_uint64
@@ -153,6 +155,17 @@ def advantages(alpha, beta, idx, reward, ddof=0, eps_norm=0.0, use_baseline=True
                                   int(bool(use_baseline)), _p(raw, _d), _p(nrm, _d),
                                   _p(st, _d))
     return raw, nrm, (float(st[0]), float(st[1]))
+
+
+def advantage_diagnostics(adv_raw, reward, tau_tight=1e-4, tau_loose=0.02):
+    """Returns [share |A|<=tau_tight, share |A|<=tau_loose, var(A), var(r)]."""
+    a = _arr(adv_raw, np.float64)
+    r = _arr(reward, np.float64)
+    assert a.shape == r.shape and a.shape[0] > 0
+    out = np.empty(4, np.float64)
+    _load().spo_oracle_advantage_diagnostics(_p(a, _d), _p(r, _d), a.shape[0], float(tau_tight),
+                                             float(tau_loose), _p(out, _d))
+    return out
 
 
 # --------------------------------------------------------------------- sampler

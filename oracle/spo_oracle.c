@@ -112,6 +112,32 @@ void spo_oracle_advantages(const double *alpha, const double *beta, int64_t N,
     }
 }
 
+/* Diagnostics of the unnormalised advantage signal (Experiments, "Signal
+ * Efficiency and Information Loss" / "Signal Stability and Advantage Variance"):
+ * share of |A| <= tau for two tolerances, variance of A and, as the "no baseline"
+ * reference, variance of the raw rewards (population variances). */
+void spo_oracle_advantage_diagnostics(const double *adv_raw, const double *reward, int32_t B,
+                                      double tau_tight, double tau_loose, double *diag)
+{
+    double n_tight = 0.0, n_loose = 0.0, sa = 0.0, sr = 0.0;
+    for (int32_t k = 0; k < B; ++k) {
+        double a = fabs(adv_raw[k]);
+        if (a <= tau_tight) n_tight += 1.0;
+        if (a <= tau_loose) n_loose += 1.0;
+        sa += adv_raw[k];
+        sr += reward[k];
+    }
+    double ma = sa / (double)B, mr = sr / (double)B, va = 0.0, vr = 0.0;
+    for (int32_t k = 0; k < B; ++k) {
+        va += (adv_raw[k] - ma) * (adv_raw[k] - ma);
+        vr += (reward[k] - mr) * (reward[k] - mr);
+    }
+    diag[0] = n_tight / (double)B;
+    diag[1] = n_loose / (double)B;
+    diag[2] = va / (double)B;
+    diag[3] = vr / (double)B;
+}
+
 /* ------------------------------------------------------------------------ */
 /* Prioritized sampling (Method, "Prioritized Prompt Sampling": the          */
 /* sampling-weight equation and the weighted draw of B prompts in the        */

@@ -19,7 +19,7 @@ SPO_W_VH, SPO_W_HV = 0, 1
 
 EXPORTS = (
     "spo_status_string", "spo_sample_prompts_workspace_bytes", "spo_sample_prompts",
-    "spo_advantages", "spo_tracker_update", "spo_tracker_init",
+    "spo_advantages", "spo_advantage_diagnostics", "spo_tracker_update", "spo_tracker_init",
     "spo_pg_loss_fwd_workspace_bytes", "spo_pg_loss_fwd",
     "spo_pg_loss_bwd_workspace_bytes", "spo_pg_loss_bwd",
     "spo_kernel_timing_enable", "spo_kernel_timing_read",
@@ -66,6 +66,8 @@ def lib():
         L.spo_sample_prompts.argtypes = [vp, vp, i64, i32, f64, u64, u64, C.c_int, u32, vp, vp, vp, sz, vp]
         L.spo_advantages.restype = C.c_int
         L.spo_advantages.argtypes = [vp, vp, i64, vp, vp, i32, C.c_int, f32, C.c_int, vp, vp, vp, vp]
+        L.spo_advantage_diagnostics.restype = C.c_int
+        L.spo_advantage_diagnostics.argtypes = [vp, vp, i32, f32, f32, vp, vp]
         L.spo_tracker_update.restype = C.c_int
         L.spo_tracker_update.argtypes = [vp, vp, i64, vp, vp, vp, i32, f32, f32, f32, C.c_int, vp, vp, vp]
         L.spo_tracker_init.restype = C.c_int
@@ -170,6 +172,17 @@ def spo_advantages(alpha, beta, idx, reward, ddof=0, eps_norm=0.0, use_baseline=
                                 float(eps_norm), int(bool(use_baseline)), _ptr(raw), _ptr(nrm), _ptr(st),
                                 _stream()), "spo_advantages")
     return raw, nrm, st
+
+
+def spo_advantage_diagnostics(adv_raw, reward, tau_tight=1e-4, tau_loose=0.02):
+    """fp32[4]: share |A|<=tau_tight, share |A|<=tau_loose, var(A), var(reward)."""
+    B = adv_raw.numel()
+    _want(adv_raw, torch.float32, "adv_raw")
+    _want(reward, torch.float32, "reward", B)
+    diag = torch.empty(4, dtype=torch.float32, device=adv_raw.device)
+    _check(lib().spo_advantage_diagnostics(_ptr(adv_raw), _ptr(reward), B, float(tau_tight), float(tau_loose),
+                                           _ptr(diag), _stream()), "spo_advantage_diagnostics")
+    return diag
 
 
 # ------------------------------------------------------------------ tracker

@@ -62,18 +62,27 @@ logits_row_lse_kernel(const T *__restrict__ logits, int64_t V, const int32_t *__
     const T *row = logits + t * V;
     float m = kNegBig, s = 0.0f;
     if (kVector) {
-        for (int64_t v = static_cast<int64_t>(threadIdx.x) * N; v < V; v += kRowThreads * N) {
-            float x[N];
-            Vec<T>::load(row + v, x);
-            float mx = x[0];
+        // four independent 16-byte loads in flight per thread before any of them is used
+        constexpr int U = 4;
+        const int64_t step = static_cast<int64_t>(kRowThreads) * N;
+        for (int64_t v0 = static_cast<int64_t>(threadIdx.x) * N; v0 < V; v0 += U * step) {
+            float x[U][N];
 #pragma unroll
-            for (int i = 1; i < N; ++i) mx = fmaxf(mx, x[i]);
-            const float nm = fmaxf(m, mx), nm2 = -nm * kLog2e;
-            float a = 0.0f;
+            for (int u = 0; u < U; ++u)
+                if (v0 + u * step < V) Vec<T>::load(row + v0 + u * step, x[u]);
 #pragma unroll
-            for (int i = 0; i < N; ++i) a += __builtin_amdgcn_exp2f(fmaf(x[i], kLog2e, nm2));
-            s = s * __builtin_amdgcn_exp2f((m - nm) * kLog2e) + a;
-            m = nm;
+            for (int u = 0; u < U; ++u) {
+                if (v0 + u * step >= V) break;
+                float mx = x[u][0];
+#pragma unroll
+                for (int i = 1; i < N; ++i) mx = fmaxf(mx, x[u][i]);
+                const float nm = fmaxf(m, mx), nm2 = -nm * kLog2e;
+                float a = 0.0f;
+#pragma unroll
+                for (int i = 0; i < N; ++i) a += __builtin_amdgcn_exp2f(fmaf(x[u][i], kLog2e, nm2));
+                s = s * __builtin_amdgcn_exp2f((m - nm) * kLog2e) + a;
+                m = nm;
+            }
         }
     } else {
         for (int64_t v = threadIdx.x; v < V; v += kRowThreads) lse_merge(m, s, Vec<T>::get(row + v), 1.0f);
@@ -105,18 +114,29 @@ logits_row_grad_kernel(const T *__restrict__ logits, int64_t V, const int32_t *_
     const float gt = g[t], nl = -lse[t] * kLog2e;
     const int64_t y = target[t];
     if (kVector) {
-        for (int64_t v = static_cast<int64_t>(threadIdx.x) * N; v < V; v += kRowThreads * N) {
-            float x[N];
+        constexpr int U = 4;
+        const int64_t step = static_cast<int64_t>(kRowThreads) * N;
+        for (int64_t v0 = static_cast<int64_t>(threadIdx.x) * N; v0 < V; v0 += U * step) {
+            float x[U][N];
             if (gt != 0.0f) {
-                Vec<T>::load(row + v, x);
 #pragma unroll
-                for (int i = 0; i < N; ++i)
-                    x[i] = (v + i == y ? gt : 0.0f) - gt * __builtin_amdgcn_exp2f(fmaf(x[i], kLog2e, nl));
-            } else {
-#pragma unroll
-                for (int i = 0; i < N; ++i) x[i] = 0.0f;
+                for (int u = 0; u < U; ++u)
+                    if (v0 + u * step < V) Vec<T>::load(row + v0 + u * step, x[u]);
             }
-            Vec<T>::store(out + v, x);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t v = v0 + u * step;
+                if (v >= V) break;
+                if (gt != 0.0f) {
+#pragma unroll
+                    for (int i = 0; i < N; ++i)
+                        x[u][i] = (v + i == y ? gt : 0.0f) - gt * __builtin_amdgcn_exp2f(fmaf(x[u][i], kLog2e, nl));
+                } else {
+#pragma unroll
+                    for (int i = 0; i < N; ++i) x[u][i] = 0.0f;
+                }
+                Vec<T>::store(out + v, x[u]);
+            }
         }
     } else {
         for (int64_t v = threadIdx.x; v < V; v += kRowThreads) {

@@ -120,9 +120,49 @@ advantages_kernel(const float *__restrict__ alpha, const float *__restrict__ bet
     }
 }
 
+// Diagnostics of the unnormalised advantages (one workgroup, fp64, fixed order).
+__global__ void __launch_bounds__(kAdvThreads)
+advantage_diagnostics_kernel(const float *__restrict__ adv_raw, const float *__restrict__ reward, int B,
+                             float tau_tight, float tau_loose, float *__restrict__ diag) {
+    __shared__ double scratch[kAdvThreads / kWave];
+    double nt = 0.0, nl = 0.0, sa = 0.0, sr = 0.0;
+    for (int k = threadIdx.x; k < B; k += kAdvThreads) {
+        const float a = fabsf(adv_raw[k]);
+        nt += a <= tau_tight ? 1.0 : 0.0;
+        nl += a <= tau_loose ? 1.0 : 0.0;
+        sa += static_cast<double>(adv_raw[k]);
+        sr += static_cast<double>(reward[k]);
+    }
+    nt = block_sum(nt, scratch);
+    nl = block_sum(nl, scratch);
+    const double ma = block_sum(sa, scratch) / B, mr = block_sum(sr, scratch) / B;
+    double va = 0.0, vr = 0.0;
+    for (int k = threadIdx.x; k < B; k += kAdvThreads) {
+        const double da = static_cast<double>(adv_raw[k]) - ma, dr = static_cast<double>(reward[k]) - mr;
+        va += da * da;
+        vr += dr * dr;
+    }
+    va = block_sum(va, scratch);
+    vr = block_sum(vr, scratch);
+    if (threadIdx.x == 0) {
+        diag[0] = static_cast<float>(nt / B);
+        diag[1] = static_cast<float>(nl / B);
+        diag[2] = static_cast<float>(va / B);
+        diag[3] = static_cast<float>(vr / B);
+    }
+}
+
 }  // namespace spo
 
 using namespace spo;
+
+extern "C" int spo_advantage_diagnostics(const float *adv_raw, const float *reward, int32_t B, float tau_tight,
+                                         float tau_loose, float *diag, spo_stream_t stream) {
+    if (!adv_raw || !reward || !diag) return SPO_ENULL;
+    if (B < 1 || !(tau_tight >= 0.0f) || !(tau_loose >= tau_tight)) return SPO_EINVAL;
+    advantage_diagnostics_kernel<<<1, kAdvThreads, 0, as_stream(stream)>>>(adv_raw, reward, B, tau_tight, tau_loose, diag);
+    return launch_status();
+}
 
 extern "C" int spo_tracker_update(float *alpha, float *beta, int64_t N, const int32_t *idx,
                                   const float *reward, const float *kl, int32_t B, float d_half,

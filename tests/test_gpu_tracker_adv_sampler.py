@@ -198,3 +198,32 @@ def test_sampler_after_update_sees_new_state(spo, oracle):
     assert np.array_equal(idx2.cpu().numpy(),
                           oracle.sample_prompts(ga.cpu().numpy(), gb.cpu().numpy(), 64, cfg.eps_explore, 0, 1))
     np.testing.assert_allclose(ga.cpu().numpy(), ea, rtol=RTOL)
+
+
+def test_advantage_diagnostics_match_oracle(spo, oracle):
+    cfg = wl.CONFIGS["C5"]
+    say("advantage_diagnostics C5 n=4096")
+    a, b, idx, r, _ = _update_case(cfg, 4096, 51)
+    raw, _, _ = spo.spo_advantages(dev(a), dev(b), dev(idx), dev(r))
+    diag = spo.spo_advantage_diagnostics(raw, dev(r), 1e-4, 0.02)
+    torch.cuda.synchronize()
+    rawc = raw.cpu().numpy()
+    want = oracle.advantage_diagnostics(rawc, r, float(np.float32(1e-4)), float(np.float32(0.02)))
+    got = diag.cpu().numpy()
+    assert got[0] == np.float32(want[0]) and got[1] == np.float32(want[1])     # counts are exact
+    np.testing.assert_allclose(got[2:], want[2:], rtol=RTOL)
+
+
+def test_tracker_update_with_general_rewards(spo, oracle):
+    cfg = wl.CONFIGS["C2"]
+    say("tracker_update non-binary rewards")
+    a, b, idx, _, kl = _update_case(cfg, 64, 61)
+    r = np.random.default_rng(61).uniform(0, 1, 64).astype(np.float32)
+    ea, eb, ev, _ = oracle.tracker_update(a, b, idx, r, kl, cfg.d_half, cfg.rho_min, cfg.rho_max)
+    ga, gb = dev(a), dev(b)
+    gv = spo.spo_tracker_update(ga, gb, dev(idx), dev(r), dev(kl), cfg.d_half, cfg.rho_min, cfg.rho_max,
+                                want_v_prev=True)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(ga.cpu().numpy(), ea, rtol=RTOL)
+    np.testing.assert_allclose(gb.cpu().numpy(), eb, rtol=RTOL)
+    np.testing.assert_allclose(gv.cpu().numpy(), ev, rtol=RTOL)

@@ -203,3 +203,35 @@ def test_dynamic_sampling_cost_constant():
     # off-path doc test of a closed form the paper prints
     p = G["dyn_sampling_p"]
     assert round(1.0 / (p * (1 - p)) - 1.0, 2) == G["dyn_sampling_cost"]
+
+
+def test_advantage_diagnostics_match_numpy(oracle):
+    rng = np.random.default_rng(3)
+    a = rng.normal(0, 0.3, 500)
+    a[:40] = rng.uniform(-1e-4, 1e-4, 40)      # inside the tight tolerance
+    a[40:120] = rng.uniform(0.001, 0.02, 80)   # inside the loose one only
+    r = rng.integers(0, 2, 500).astype(float)
+    d = oracle.advantage_diagnostics(a, r, 1e-4, 0.02)
+    assert d[0] == np.mean(np.abs(a) <= 1e-4) and d[0] >= 40 / 500
+    assert d[1] == np.mean(np.abs(a) <= 0.02) and d[1] >= 120 / 500
+    assert d[2] == pytest.approx(np.var(a), rel=1e-13)
+    assert d[3] == pytest.approx(np.var(r), rel=1e-13)
+    # a perfect baseline halves nothing and removes everything: A = r - p has variance p(1-p),
+    # the raw reward of a prompt mix has variance >= that (law of total variance)
+    p = rng.uniform(0, 1, 20000)
+    r = (rng.random(20000) < p).astype(float)
+    d = oracle.advantage_diagnostics(r - p, r)
+    assert d[2] < d[3]
+    assert d[2] == pytest.approx(np.mean(p * (1 - p)), rel=0.05)
+
+
+def test_general_rewards_follow_the_same_ema(oracle):
+    # non-binary rewards in [0, 1]: the same update keeps v = alpha/(alpha+beta) on the EMA
+    rng = np.random.default_rng(4)
+    N = 32
+    a, b = rng.uniform(0.5, 20, N), rng.uniform(0.5, 20, N)
+    r = rng.uniform(0, 1, N)
+    kl = rng.exponential(0.02, N)
+    a2, b2, vprev, rho = oracle.tracker_update(a, b, np.arange(N, dtype=np.int32), r, kl, 0.25, 0.875, 0.96)
+    np.testing.assert_allclose(a2 / (a2 + b2), vprev + (r - vprev) / (rho * (a + b) + 1.0), rtol=1e-13)
+    np.testing.assert_allclose(a2 + b2, rho * (a + b) + 1.0, rtol=1e-14)
