@@ -29,7 +29,7 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 # scaled by what the same counter reads for a plain 1 GiB copy (profiles/step_c3_hbm_traffic.md).
 # Valid only for the kernels as profiled: None for any other workload or chunk size.
 TRAFFIC_BYTES_PER_LAUNCH = {
-    ("C3", 0): {"fwd_sweep": None, "bwd_recompute": None, "bwd_dhidden": None, "bwd_dw": None},
+    ("C3", 0): {"fwd_sweep": 865.6e9, "bwd_recompute": 92.1e9, "bwd_dhidden": 71.0e9, "bwd_dw": 74.0e9},
 }
 
 
@@ -51,7 +51,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py measures one GPU: the path is built and measured on a single MI355X "
-            "(it shards by responses; see DESIGN.md). Run with --gpus 1.")
+            "(across GPUs it would shard by responses). Run with --gpus 1.")
         return 2
 
     import numpy as np
