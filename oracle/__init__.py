@@ -6,8 +6,8 @@ imports nothing from the product package.  Each function marshals numpy arrays
 into the C routine of the same name; all arithmetic lives in the C file, which
 states the passage of the paper every routine follows.
 
-Parity unpinned: ``philox4x32_10`` (no independent known answer available);
-everything else is pinned by ``tests/test_oracle_*.py``.
+Every function is pinned by ``tests/test_oracle_*.py`` (``philox4x32_10`` by
+the generator's published known-answer vectors).
 """
 from __future__ import annotations
 

@@ -33,11 +33,22 @@ def test_weight_codes_and_cdf(oracle):
     assert np.array_equal(oracle.weight_cdf(a, b, 0.05), np.cumsum(codes))
 
 
+def test_philox_known_answers(oracle):
+    # The published known-answer vectors of the generator (tests/golden/philox4x32_10_kat.txt).
+    import pathlib
+    rows = [ln.split() for ln in (pathlib.Path(__file__).parent / "golden" / "philox4x32_10_kat.txt").read_text().splitlines()
+            if ln.strip() and not ln.startswith("#")]
+    assert len(rows) == 3
+    for row in rows:
+        words = [int(x, 16) for x in row]
+        out = oracle.philox4x32_10(words[0:4], words[4:6])
+        assert [int(x) for x in out] == words[6:10]
+
+
 def test_philox_is_a_keyed_bijection_with_good_bits(oracle):
-    # Parity unpinned (no known-answer vector available here).  What can be
-    # checked: determinism, distinct counters give distinct blocks, key and
-    # counter both matter, bits are balanced, one flipped input bit flips about
-    # half of the output bits.
+    # Beyond the known answers: determinism, distinct counters give distinct
+    # blocks, key and counter both matter, bits are balanced, one flipped input
+    # bit flips about half of the output bits.
     key = np.array([7, 9], np.uint32)
     outs = np.array([oracle.philox4x32_10([i, 0, 0, 0], key) for i in range(4096)])
     assert np.array_equal(outs[5], oracle.philox4x32_10([5, 0, 0, 0], key))
