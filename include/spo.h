@@ -92,7 +92,9 @@ int spo_sample_prompts(const float *alpha, const float *beta, int64_t N, int32_t
  * global normalisation (A - mu_B) / sigma_B over the whole batch).  One value per
  * response; the loss applies it to every token of that response.
  *
- * alpha, beta  [N] fp32 tracker state before this iteration's update.
+ * alpha, beta  [N] fp32 tracker state before this iteration's update.  beta may
+ *              be NULL: alpha then holds the estimate v_hat itself (the state of
+ *              spo_tracker_update_ema).
  * idx, reward  [B]: prompt id and reward of each response.
  * ddof         0 = population standard deviation (the default reading), 1 = sample.
  * eps_norm     added to sigma in the denominator (0 for the paper's form).
@@ -138,6 +140,24 @@ int spo_tracker_update(float *alpha, float *beta, int64_t N, const int32_t *idx,
                        const float *reward, const float *kl, int32_t B, float d_half,
                        float rho_min, float rho_max, int ids_unique, uint32_t *n_obs,
                        float *v_prev_out, spo_stream_t stream);
+
+/* ---------------------------------------------------------------------------
+ * The tracker in its moving-average form, for rewards that are not binary
+ * (Method, "A KL-Adaptive Value Tracker": the EMA form of the update and the
+ * remark on general rewards).  State per prompt: the estimate v_hat and the
+ * effective sample size n_eff (alpha + beta of the Beta form):
+ *     eta = 1 / (rho * n_eff + 1),  v_hat <- v_hat + eta * (r - v_hat),
+ *     n_eff <- rho * n_eff + 1,
+ * with rho as in spo_tracker_update.  With v_hat = alpha / (alpha + beta) and
+ * n_eff = alpha + beta the two forms describe the same estimate; this one puts
+ * no bound on r.  All other arguments, the fp64-then-one-rounding arithmetic,
+ * limits and errors are those of spo_tracker_update.  spo_advantages accepts the
+ * state of this form as alpha = v_hat, beta = NULL.
+ * ------------------------------------------------------------------------- */
+int spo_tracker_update_ema(float *v_hat, float *n_eff, int64_t N, const int32_t *idx,
+                           const float *reward, const float *kl, int32_t B, float d_half,
+                           float rho_min, float rho_max, int ids_unique, uint32_t *n_obs,
+                           float *v_prev_out, spo_stream_t stream);
 
 /* Tracker initialisation (Method, "Initialization"; Appendix "SPO
  * Initialization"): N0 = 1/(1 - rho_min), alpha0 = N0*v0, beta0 = N0*(1 - v0),

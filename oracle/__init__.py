@@ -54,6 +54,9 @@ def _load():
             lib.spo_oracle_tracker_update.argtypes = [
                 _d, _d, C.c_int64, _i32, _d, _d, C.c_int32, C.c_double, C.c_double,
                 C.c_double, _d, _d]
+            lib.spo_oracle_tracker_update_ema.restype = None
+            lib.spo_oracle_tracker_update_ema.argtypes = [
+                _d, _d, C.c_int64, _i32, _d, _d, C.c_int32, C.c_double, C.c_double, C.c_double, _d]
             lib.spo_oracle_tracker_init.restype = None
             lib.spo_oracle_tracker_init.argtypes = [_d, C.c_int64, C.c_double, _d, _d]
             lib.spo_oracle_advantages.restype = None
@@ -130,6 +133,23 @@ def tracker_update(alpha, beta, idx, reward, kl, d_half, rho_min, rho_max):
     return a, b, vprev, rho
 
 
+def tracker_update_ema(v_hat, n_eff, idx, reward, kl, d_half, rho_min, rho_max):
+    """Moving-average form. Returns (v', n_eff', v_prev[B]); inputs are not modified."""
+    v = _arr(v_hat, np.float64).copy()
+    n = _arr(n_eff, np.float64).copy()
+    idx = _arr(idx, np.int32)
+    r = _arr(reward, np.float64)
+    k = _arr(kl, np.float64)
+    B = idx.shape[0]
+    assert r.shape[0] == B and k.shape[0] == B and v.shape == n.shape
+    assert B == 0 or (idx.min() >= 0 and idx.max() < v.shape[0])
+    vprev = np.empty(B, np.float64)
+    _load().spo_oracle_tracker_update_ema(_p(v, _d), _p(n, _d), v.shape[0], _p(idx, _i32),
+                                          _p(r, _d), _p(k, _d), B, d_half, rho_min, rho_max,
+                                          _p(vprev, _d))
+    return v, n, vprev
+
+
 def tracker_init(v0, rho_min):
     v = _arr(v0, np.float64)
     a = np.empty_like(v)
@@ -140,9 +160,10 @@ def tracker_init(v0, rho_min):
 
 # ------------------------------------------------------------------ advantages
 def advantages(alpha, beta, idx, reward, ddof=0, eps_norm=0.0, use_baseline=True):
-    """Returns (adv_raw[B], adv_norm[B], (mu, sigma))."""
+    """Returns (adv_raw[B], adv_norm[B], (mu, sigma)).  ``beta=None``: ``alpha``
+    holds the value estimate itself (moving-average form of the tracker)."""
     a = _arr(alpha, np.float64)
-    b = _arr(beta, np.float64)
+    b = None if beta is None else _arr(beta, np.float64)
     idx = _arr(idx, np.int32)
     r = _arr(reward, np.float64)
     B = idx.shape[0]
@@ -150,7 +171,7 @@ def advantages(alpha, beta, idx, reward, ddof=0, eps_norm=0.0, use_baseline=True
     raw = np.empty(B, np.float64)
     nrm = np.empty(B, np.float64)
     st = np.zeros(2, np.float64)
-    _load().spo_oracle_advantages(_p(a, _d), _p(b, _d), a.shape[0], _p(idx, _i32),
+    _load().spo_oracle_advantages(_p(a, _d), None if b is None else _p(b, _d), a.shape[0], _p(idx, _i32),
                                   _p(r, _d), B, int(ddof), float(eps_norm),
                                   int(bool(use_baseline)), _p(raw, _d), _p(nrm, _d),
                                   _p(st, _d))

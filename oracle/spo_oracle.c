@@ -64,6 +64,29 @@ void spo_oracle_tracker_update(double *alpha, double *beta, int64_t N,
     }
 }
 
+/* The same tracker in its moving-average form, for rewards that are not binary
+ * (Method, "A KL-Adaptive Value Tracker", the EMA form and the remark on general
+ * rewards): the state is the estimate v and the effective sample size n,
+ *     eta = 1 / (rho * n + 1),  v <- v + eta * (r - v),  n <- rho * n + 1,
+ * where n before the update is the effective size before it (alpha + beta of the
+ * Beta form before the observation; with that reading the two forms agree).
+ * Sequential in batch order; v_prev[k] (may be NULL) is v before observation k. */
+void spo_oracle_tracker_update_ema(double *v, double *n_eff, int64_t N,
+                                   const int32_t *idx, const double *reward,
+                                   const double *kl, int32_t B, double d_half,
+                                   double rho_min, double rho_max, double *v_prev)
+{
+    (void)N;
+    for (int32_t k = 0; k < B; ++k) {
+        int64_t i = idx[k];
+        double rho = spo_oracle_discount(kl[k], d_half, rho_min, rho_max);
+        double eta = 1.0 / (rho * n_eff[i] + 1.0);
+        if (v_prev) v_prev[k] = v[i];
+        v[i] = v[i] + eta * (reward[k] - v[i]);
+        n_eff[i] = rho * n_eff[i] + 1.0;
+    }
+}
+
 /* Initialisation (Method, "Initialization"; Appendix "SPO Initialization"):
  * N0 = 1/(1-rho_min), alpha0 = N0*v0, beta0 = N0*(1-v0). */
 void spo_oracle_tracker_init(const double *v0, int64_t N, double rho_min,
@@ -91,7 +114,9 @@ void spo_oracle_advantages(const double *alpha, const double *beta, int64_t N,
     double sum = 0.0;
     for (int32_t k = 0; k < B; ++k) {
         int64_t i = idx[k];
-        double v = use_baseline ? alpha[i] / (alpha[i] + beta[i]) : 0.0;
+        double v = 0.0; /* "no baseline" ablation */
+        if (use_baseline) /* beta == NULL: alpha holds the estimate itself (EMA form) */
+            v = beta ? alpha[i] / (alpha[i] + beta[i]) : alpha[i];
         adv_raw[k] = reward[k] - v;
         sum += adv_raw[k];
     }

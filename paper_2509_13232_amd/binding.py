@@ -19,7 +19,8 @@ SPO_W_VH, SPO_W_HV = 0, 1
 
 EXPORTS = (
     "spo_status_string", "spo_sample_prompts_workspace_bytes", "spo_sample_prompts",
-    "spo_advantages", "spo_advantage_diagnostics", "spo_tracker_update", "spo_tracker_init",
+    "spo_advantages", "spo_advantage_diagnostics", "spo_tracker_update", "spo_tracker_update_ema",
+    "spo_tracker_init",
     "spo_pg_loss_fwd_workspace_bytes", "spo_pg_loss_fwd",
     "spo_pg_loss_bwd_workspace_bytes", "spo_pg_loss_bwd",
     "spo_kernel_timing_enable", "spo_kernel_timing_read",
@@ -70,6 +71,8 @@ def lib():
         L.spo_advantage_diagnostics.argtypes = [vp, vp, i32, f32, f32, vp, vp]
         L.spo_tracker_update.restype = C.c_int
         L.spo_tracker_update.argtypes = [vp, vp, i64, vp, vp, vp, i32, f32, f32, f32, C.c_int, vp, vp, vp]
+        L.spo_tracker_update_ema.restype = C.c_int
+        L.spo_tracker_update_ema.argtypes = L.spo_tracker_update.argtypes
         L.spo_tracker_init.restype = C.c_int
         L.spo_tracker_init.argtypes = [vp, i64, f32, vp, vp, vp]
         L.spo_pg_loss_fwd_workspace_bytes.restype = sz
@@ -162,7 +165,7 @@ def spo_advantages(alpha, beta, idx, reward, ddof=0, eps_norm=0.0, use_baseline=
     _want(reward, torch.float32, "reward")
     if use_baseline:
         _want(alpha, torch.float32, "alpha")
-        _want(beta, torch.float32, "beta", alpha.numel())
+        _want(beta, torch.float32, "beta", alpha.numel())  # None: alpha holds v_hat itself
         _want(idx, torch.int32, "idx", B)
     N = alpha.numel() if alpha is not None else 0
     raw = torch.empty(B, dtype=torch.float32, device=reward.device)
@@ -200,6 +203,23 @@ def spo_tracker_update(alpha, beta, idx, reward, kl, d_half, rho_min, rho_max, i
     _check(lib().spo_tracker_update(_ptr(alpha), _ptr(beta), N, _ptr(idx), _ptr(reward), _ptr(kl), B,
                                     float(d_half), float(rho_min), float(rho_max), int(bool(ids_unique)),
                                     _ptr(n_obs), _ptr(vprev), _stream()), "spo_tracker_update")
+    return vprev
+
+
+def spo_tracker_update_ema(v_hat, n_eff, idx, reward, kl, d_half, rho_min, rho_max, ids_unique=True,
+                           n_obs=None, want_v_prev=False):
+    """Moving-average form: updates v_hat and n_eff IN PLACE; returns v_prev[B] when asked."""
+    N, B = v_hat.numel(), idx.numel()
+    _want(v_hat, torch.float32, "v_hat")
+    _want(n_eff, torch.float32, "n_eff", N)
+    _want(idx, torch.int32, "idx")
+    _want(reward, torch.float32, "reward", B)
+    _want(kl, torch.float32, "kl", B)
+    _want(n_obs, torch.int32, "n_obs", N)
+    vprev = torch.empty(B, dtype=torch.float32, device=v_hat.device) if want_v_prev else None
+    _check(lib().spo_tracker_update_ema(_ptr(v_hat), _ptr(n_eff), N, _ptr(idx), _ptr(reward), _ptr(kl), B,
+                                        float(d_half), float(rho_min), float(rho_max), int(bool(ids_unique)),
+                                        _ptr(n_obs), _ptr(vprev), _stream()), "spo_tracker_update_ema")
     return vprev
 
 

@@ -22,7 +22,30 @@ __device__ __forceinline__ void observe(float &a, float &b, float r, double rho)
     b = static_cast<float>(rho * static_cast<double>(b) + (1.0 - rd));
 }
 
+// Moving-average form: v <- v + (r - v)/(rho n + 1), n <- rho n + 1.
+__device__ __forceinline__ void observe_ema(float &v, float &n, float r, double rho) {
+    const double vd = static_cast<double>(v), nd = static_cast<double>(n);
+    const double eta = 1.0 / (rho * nd + 1.0);
+    v = static_cast<float>(vd + eta * (static_cast<double>(r) - vd));
+    n = static_cast<float>(rho * nd + 1.0);
+}
+
+// Both forms of the tracker share the update kernels: Ema = false keeps
+// (alpha, beta), Ema = true keeps (v_hat, n_eff) in the same two arrays.
+template <bool Ema>
+__device__ __forceinline__ float mean_of(float a, float b) {
+    if constexpr (Ema) return a;
+    return static_cast<float>(static_cast<double>(a) / (static_cast<double>(a) + static_cast<double>(b)));
+}
+
+template <bool Ema>
+__device__ __forceinline__ void apply(float &a, float &b, float r, double rho) {
+    if constexpr (Ema) observe_ema(a, b, r, rho);
+    else observe(a, b, r, rho);
+}
+
 // One thread per observation; ids are unique, so every thread owns its entry.
+template <bool Ema>
 __global__ void __launch_bounds__(256)
 tracker_update_unique_kernel(float *__restrict__ alpha, float *__restrict__ beta,
                              const int32_t *__restrict__ idx, const float *__restrict__ reward,
@@ -33,8 +56,8 @@ tracker_update_unique_kernel(float *__restrict__ alpha, float *__restrict__ beta
     if (k >= B) return;
     const int64_t i = idx[k];
     float a = alpha[i], b = beta[i];
-    if (v_prev) v_prev[k] = static_cast<float>(static_cast<double>(a) / (static_cast<double>(a) + static_cast<double>(b)));
-    observe(a, b, reward[k], discount(kl[k], d_half, rho_min, rho_max));
+    if (v_prev) v_prev[k] = mean_of<Ema>(a, b);
+    apply<Ema>(a, b, reward[k], discount(kl[k], d_half, rho_min, rho_max));
     alpha[i] = a;
     beta[i] = b;
     if (n_obs) n_obs[i] += 1u;
@@ -42,6 +65,7 @@ tracker_update_unique_kernel(float *__restrict__ alpha, float *__restrict__ beta
 
 // Repeated ids: the thread of the FIRST occurrence of an id applies all of its
 // observations one after the other in batch order; other threads do nothing.
+template <bool Ema>
 __global__ void __launch_bounds__(256)
 tracker_update_ordered_kernel(float *__restrict__ alpha, float *__restrict__ beta,
                               const int32_t *__restrict__ idx, const float *__restrict__ reward,
@@ -57,8 +81,8 @@ tracker_update_ordered_kernel(float *__restrict__ alpha, float *__restrict__ bet
     uint32_t seen = 0;
     for (int j = k; j < B; ++j) {
         if (idx[j] != id) continue;
-        if (v_prev) v_prev[j] = static_cast<float>(static_cast<double>(a) / (static_cast<double>(a) + static_cast<double>(b)));
-        observe(a, b, reward[j], discount(kl[j], d_half, rho_min, rho_max));
+        if (v_prev) v_prev[j] = mean_of<Ema>(a, b);
+        apply<Ema>(a, b, reward[j], discount(kl[j], d_half, rho_min, rho_max));
         ++seen;
     }
     alpha[id] = a;
@@ -91,8 +115,8 @@ advantages_kernel(const float *__restrict__ alpha, const float *__restrict__ bet
         double v = 0.0;
         if (use_baseline) {
             const int64_t i = idx[k];
-            const double a = alpha[i], b = beta[i];
-            v = a / (a + b);
+            const double a = alpha[i];
+            v = beta ? a / (a + static_cast<double>(beta[i])) : a;
         }
         return static_cast<double>(reward[k]) - v;
     };
@@ -164,22 +188,39 @@ extern "C" int spo_advantage_diagnostics(const float *adv_raw, const float *rewa
     return launch_status();
 }
 
-extern "C" int spo_tracker_update(float *alpha, float *beta, int64_t N, const int32_t *idx,
-                                  const float *reward, const float *kl, int32_t B, float d_half,
-                                  float rho_min, float rho_max, int ids_unique, uint32_t *n_obs,
-                                  float *v_prev_out, spo_stream_t stream) {
+template <bool Ema>
+static int tracker_update_launch(float *alpha, float *beta, int64_t N, const int32_t *idx,
+                                 const float *reward, const float *kl, int32_t B, float d_half,
+                                 float rho_min, float rho_max, int ids_unique, uint32_t *n_obs,
+                                 float *v_prev_out, spo_stream_t stream) {
     if (!alpha || !beta || !idx || !reward || !kl) return SPO_ENULL;
     if (N < 1 || N >= (int64_t(1) << 31) || B < 1) return SPO_EINVAL;
     if (!(d_half > 0.0f) || !(rho_min >= 0.0f) || !(rho_max <= 1.0f) || !(rho_min <= rho_max))
         return SPO_EINVAL;
     const int threads = 256, blocks = (B + threads - 1) / threads;
     if (ids_unique)
-        tracker_update_unique_kernel<<<blocks, threads, 0, as_stream(stream)>>>(
+        tracker_update_unique_kernel<Ema><<<blocks, threads, 0, as_stream(stream)>>>(
             alpha, beta, idx, reward, kl, B, d_half, rho_min, rho_max, n_obs, v_prev_out);
     else
-        tracker_update_ordered_kernel<<<blocks, threads, 0, as_stream(stream)>>>(
+        tracker_update_ordered_kernel<Ema><<<blocks, threads, 0, as_stream(stream)>>>(
             alpha, beta, idx, reward, kl, B, d_half, rho_min, rho_max, n_obs, v_prev_out);
     return launch_status();
+}
+
+extern "C" int spo_tracker_update(float *alpha, float *beta, int64_t N, const int32_t *idx,
+                                  const float *reward, const float *kl, int32_t B, float d_half,
+                                  float rho_min, float rho_max, int ids_unique, uint32_t *n_obs,
+                                  float *v_prev_out, spo_stream_t stream) {
+    return tracker_update_launch<false>(alpha, beta, N, idx, reward, kl, B, d_half, rho_min, rho_max,
+                                        ids_unique, n_obs, v_prev_out, stream);
+}
+
+extern "C" int spo_tracker_update_ema(float *v_hat, float *n_eff, int64_t N, const int32_t *idx,
+                                      const float *reward, const float *kl, int32_t B, float d_half,
+                                      float rho_min, float rho_max, int ids_unique, uint32_t *n_obs,
+                                      float *v_prev_out, spo_stream_t stream) {
+    return tracker_update_launch<true>(v_hat, n_eff, N, idx, reward, kl, B, d_half, rho_min, rho_max,
+                                       ids_unique, n_obs, v_prev_out, stream);
 }
 
 extern "C" int spo_tracker_init(const float *v0, int64_t N, float rho_min, float *alpha,
@@ -199,7 +240,7 @@ extern "C" int spo_advantages(const float *alpha, const float *beta, int64_t N, 
                               int use_baseline, float *adv_raw, float *adv_norm, float *stats,
                               spo_stream_t stream) {
     if (!reward || !adv_norm) return SPO_ENULL;
-    if (use_baseline && (!alpha || !beta || !idx)) return SPO_ENULL;
+    if (use_baseline && (!alpha || !idx)) return SPO_ENULL;
     if (B < 1 || (use_baseline && N < 1) || ddof < 0 || ddof > 1 || !(eps_norm >= 0.0f))
         return SPO_EINVAL;
     advantages_kernel<<<1, kAdvThreads, 0, as_stream(stream)>>>(

@@ -227,3 +227,42 @@ def test_tracker_update_with_general_rewards(spo, oracle):
     np.testing.assert_allclose(ga.cpu().numpy(), ea, rtol=RTOL)
     np.testing.assert_allclose(gb.cpu().numpy(), eb, rtol=RTOL)
     np.testing.assert_allclose(gv.cpu().numpy(), ev, rtol=RTOL)
+
+
+@pytest.mark.parametrize("unique", [True, False])
+def test_tracker_update_ema_matches_oracle(spo, oracle, unique):
+    # moving-average form of the tracker, rewards outside [0, 1]
+    cfg = wl.CONFIGS["C5"]
+    say(f"tracker_update_ema unique={unique}")
+    rng = np.random.default_rng(71)
+    N, B = 4096, 1500
+    v = rng.uniform(-1, 3, N).astype(np.float32)
+    n = rng.uniform(1, 25, N).astype(np.float32)
+    idx = (rng.permutation(N)[:B] if unique else rng.integers(0, 64, B)).astype(np.int32)
+    r = rng.normal(1.0, 2.0, B).astype(np.float32)
+    kl = rng.exponential(0.02, B).astype(np.float32)
+    ev, en, evp = oracle.tracker_update_ema(v, n, idx, r, kl, cfg.d_half, cfg.rho_min, cfg.rho_max)
+    gv, gn = dev(v), dev(n)
+    cnt = torch.zeros(N, dtype=torch.int32, device="cuda")
+    gvp = spo.spo_tracker_update_ema(gv, gn, dev(idx), dev(r), dev(kl), cfg.d_half, cfg.rho_min, cfg.rho_max,
+                                     ids_unique=unique, n_obs=cnt, want_v_prev=True)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(gv.cpu().numpy(), ev, rtol=RTOL, atol=1e-6)
+    np.testing.assert_allclose(gn.cpu().numpy(), en, rtol=RTOL)
+    np.testing.assert_allclose(gvp.cpu().numpy(), evp, rtol=RTOL, atol=1e-6)
+    assert np.array_equal(cnt.cpu().numpy(), np.bincount(idx, minlength=N))
+
+
+def test_advantages_from_the_estimate_itself(spo, oracle):
+    say("advantages with beta=None")
+    rng = np.random.default_rng(72)
+    N, B = 512, 200
+    v = rng.uniform(-1, 3, N).astype(np.float32)
+    idx = rng.permutation(N)[:B].astype(np.int32)
+    r = rng.normal(1.0, 2.0, B).astype(np.float32)
+    eraw, enrm, est = oracle.advantages(v, None, idx, r)
+    raw, nrm, st = spo.spo_advantages(dev(v), None, dev(idx), dev(r))
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(raw.cpu().numpy(), eraw, rtol=RTOL, atol=1e-6)
+    np.testing.assert_allclose(nrm.cpu().numpy(), enrm, rtol=RTOL, atol=1e-6)
+    np.testing.assert_allclose(st.cpu().numpy(), est, rtol=RTOL)

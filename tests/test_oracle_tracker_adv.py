@@ -235,3 +235,51 @@ def test_general_rewards_follow_the_same_ema(oracle):
     a2, b2, vprev, rho = oracle.tracker_update(a, b, np.arange(N, dtype=np.int32), r, kl, 0.25, 0.875, 0.96)
     np.testing.assert_allclose(a2 / (a2 + b2), vprev + (r - vprev) / (rho * (a + b) + 1.0), rtol=1e-13)
     np.testing.assert_allclose(a2 + b2, rho * (a + b) + 1.0, rtol=1e-14)
+
+
+def test_ema_form_is_a_discounted_weighted_mean(oracle):
+    # Closed form: with constant discount rho the moving-average form is the
+    # weighted mean (rho^k n0 v0 + sum_j rho^(k-1-j) r_j) / (rho^k n0 + sum_j rho^(k-1-j)),
+    # in exact rationals, for rewards that are neither binary nor inside [0, 1].
+    rho = Fraction(7, 8)
+    v0, n0 = Fraction(1, 4), Fraction(8)
+    rs = [Fraction(5, 2), Fraction(-3), Fraction(0), Fraction(7, 3), Fraction(1, 10)]
+    v, n = np.array([float(v0)]), np.array([float(n0)])
+    num, den = n0 * v0, n0
+    for r in rs:
+        v, n, vprev = oracle.tracker_update_ema(v, n, [0], [float(r)], [10.0], 0.25, float(rho), 0.96)
+        assert vprev[0] == pytest.approx(float(num / den), rel=1e-14)
+        num, den = rho * num + r, rho * den + 1
+        assert v[0] == pytest.approx(float(num / den), rel=1e-14)
+        assert n[0] == pytest.approx(float(den), rel=1e-15)
+    # rho = 1: the plain running mean with the prior counted n0 times
+    v, n, _ = oracle.tracker_update_ema([0.5] * 1, [2.0], [0, 0, 0], [4.0, -1.0, 9.0], [0.0] * 3, 0.25, 1.0, 1.0)
+    assert v[0] == pytest.approx((2.0 * 0.5 + 12.0) / 5.0, rel=1e-15) and n[0] == 5.0
+
+
+def test_ema_form_agrees_with_the_beta_form(oracle):
+    # v = alpha/(alpha+beta), n = alpha+beta: both forms track the same estimate,
+    # also through repeated ids and both clamps of the discount.
+    rng = np.random.default_rng(8)
+    N, B = 16, 200
+    a, b = rng.uniform(0.5, 20, N), rng.uniform(0.5, 20, N)
+    idx = rng.integers(0, N, B).astype(np.int32)
+    r = rng.integers(0, 2, B).astype(np.float64)
+    kl = rng.exponential(0.03, B)
+    a2, b2, vp_beta, _ = oracle.tracker_update(a, b, idx, r, kl, 0.25, 0.875, 0.96)
+    v2, n2, vp_ema = oracle.tracker_update_ema(a / (a + b), a + b, idx, r, kl, 0.25, 0.875, 0.96)
+    np.testing.assert_allclose(v2, a2 / (a2 + b2), rtol=1e-12)
+    np.testing.assert_allclose(n2, a2 + b2, rtol=1e-12)
+    np.testing.assert_allclose(vp_ema, vp_beta, rtol=1e-12)
+
+
+def test_advantages_accept_the_estimate_itself(oracle):
+    rng = np.random.default_rng(9)
+    a, b = rng.uniform(0.5, 20, 32), rng.uniform(0.5, 20, 32)
+    idx = rng.permutation(32)[:12].astype(np.int32)
+    r = rng.uniform(-2, 2, 12)
+    raw1, nrm1, st1 = oracle.advantages(a, b, idx, r)
+    raw2, nrm2, st2 = oracle.advantages(a / (a + b), None, idx, r)
+    np.testing.assert_allclose(raw2, raw1, rtol=1e-13)
+    np.testing.assert_allclose(nrm2, nrm1, rtol=1e-12)
+    np.testing.assert_allclose(raw2, r - (a / (a + b))[idx], rtol=1e-15)
