@@ -222,10 +222,18 @@ recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, in
 #pragma unroll
                     for (int fn = 0; fn < TL::FN; ++fn) acc[fm][fn][r] = kNegBig;
     }
+    // The vocabulary-contiguous copy goes through LDS (the operand stages are free now):
+    // a lane holds 4 consecutive vocabulary entries of ONE token, so stored directly a
+    // wavefront would scatter 64 pieces of 8 bytes over 64 rows per instruction.  The tile
+    // is laid out as 256 token rows of 512 bytes, 16-byte chunk c of row t at position
+    // c ^ (t % 32) (conflict-free both for the writes below and the row reads after).
+    const int lane = threadIdx.x & 63;
     const int quad_lane = threadIdx.x & 3;
+    char *ztile = lds;
 #pragma unroll
     for (int fn = 0; fn < TL::FN; ++fn) {
-        const int64_t t = n0 + TL::acc_col(fn);
+        const int tl = TL::wave_n0() + fn * 32 + (lane & 31);
+        const int64_t t = n0 + tl;
         const bool tok_ok = t < T_valid;
         const float gt = tok_ok ? g[t] : 0.0f;
         const float ngt = -gt;
@@ -233,13 +241,14 @@ recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, in
         const float nl = tok_ok ? -lse[t] * kLog2e : kNegBig;
         // distance of the target's vocabulary row from this wave's first row
         const int dy = (tok_ok ? target[t] : -1) - static_cast<int>(m0 + TL::wave_m0());
-        const bool mine = static_cast<unsigned>(dy) < static_cast<unsigned>(TL::WM) && ((dy >> 2) & 1) == ((threadIdx.x & 63) >> 5);
+        const bool mine = static_cast<unsigned>(dy) < static_cast<unsigned>(TL::WM) && ((dy >> 2) & 1) == (lane >> 5);
         const int fq = dy >> 5, rq = ((dy & 31) >> 3) * 4 + (dy & 3);
 #pragma unroll
         for (int fm = 0; fm < TL::FM; ++fm) {
 #pragma unroll
             for (int r4 = 0; r4 < 4; ++r4) {
-                const int64_t v0 = m0 + TL::acc_row(fm, r4 * 4);
+                const int vl = TL::wave_m0() + fm * 32 + r4 * 8 + 4 * (lane >> 5);  // first of my 4 rows, tile-local
+                const int64_t v0 = m0 + vl;
                 float dz[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
@@ -250,11 +259,11 @@ recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, in
                         if ((rq & 3) == i) dz[i] += gt;
                 }
                 const uint32_t x = pack_bf16x2_rn(dz[0], dz[1]), y = pack_bf16x2_rn(dz[2], dz[3]);
-                if (dZ && v0 < V_pad) {
+                if (dZ) {
                     uint2 pk;
                     pk.x = x;
                     pk.y = y;
-                    *reinterpret_cast<uint2 *>(dZ + t * ldz + v0) = pk;
+                    *reinterpret_cast<uint2 *>(ztile + tl * 512 + (((vl >> 3) ^ (tl & 31)) << 4) + (vl & 4) * 2) = pk;
                 }
                 if (dZT) {
                     // The four lanes of a quad hold four consecutive tokens of the same four
@@ -280,6 +289,18 @@ recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, in
                     if (vr < V) *reinterpret_cast<uint2 *>(dZT + vr * ldzt + tq) = row;
                 }
             }
+        }
+    }
+    if (dZ) {
+        __syncthreads();
+        // every wavefront writes 32 token rows, two rows (2 x 512 contiguous bytes) per store
+        const int ci = lane & 31;
+        const bool col_ok = m0 + ci * 8 < V_pad;
+#pragma unroll
+        for (int i = 0; i < TL::BN / TL::NWAVE / 2; ++i) {
+            const int tl = TL::wave_id() * (TL::BN / TL::NWAVE) + 2 * i + (lane >> 5);
+            const uint4 v = *reinterpret_cast<const uint4 *>(ztile + tl * 512 + ((ci ^ (tl & 31)) << 4));
+            if (col_ok) *reinterpret_cast<uint4 *>(dZ + (n0 + tl) * ldz + m0 + ci * 8) = v;
         }
     }
 }
