@@ -85,6 +85,87 @@ __global__ void __launch_bounds__(256) fill_zero_kernel(uint32_t *__restrict__ p
 }
 
 // ----------------------------------------------------------------------------
+// backward: compaction of the tokens that carry a gradient
+// ----------------------------------------------------------------------------
+// Masked tokens, tokens on the clipped branch and tokens of a response with zero
+// advantage have g = 0: their rows of dZ vanish, so the backward contractions run
+// over the remaining ("active") tokens only, in their original order.
+
+// act_idx[j] = index of the j-th token with g != 0; n_act[0] = their number.
+// One workgroup walks the tokens 4096 at a time (order-preserving, deterministic).
+__global__ void __launch_bounds__(1024)
+compact_active_kernel(const float *__restrict__ g, int64_t T, int32_t *__restrict__ act_idx,
+                      int32_t *__restrict__ n_act) {
+    __shared__ int wave_cnt[16];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int base = 0;
+    for (int64_t t0 = 0; t0 < T; t0 += 4096) {
+        const int64_t t = t0 + threadIdx.x * 4;
+        bool on[4];
+        int mine = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            on[i] = t + i < T && g[t + i] != 0.0f;
+            mine += on[i] ? 1 : 0;
+        }
+        // exclusive prefix of `mine` over the wavefront, then over the 16 wavefronts
+        int incl = mine;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const int up = __shfl_up(incl, d, kWave);
+            if (lane >= d) incl += up;
+        }
+        if (lane == kWave - 1) wave_cnt[wave] = incl;
+        __syncthreads();
+        int off = 0, tot = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            const int c = wave_cnt[w];
+            off += w < wave ? c : 0;
+            tot += c;
+        }
+        int pos = base + off + incl - mine;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (on[i]) act_idx[pos++] = static_cast<int32_t>(t + i);
+        base += tot;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) n_act[0] = base;
+}
+
+// Number of active tokens that fall into rows [row_base, row_base + cap) of the compact order.
+__device__ __forceinline__ int64_t active_rows(const int32_t *n_act, int64_t row_base, int64_t cap) {
+    const int64_t n = static_cast<int64_t>(*n_act) - row_base;
+    return n < 0 ? 0 : (n > cap ? cap : n);
+}
+
+// Rows [row_base, row_base + rows) of the compact order as contiguous copies: the hidden
+// states (Xc[r] = X[act_idx[row_base + r]]) and the per-token scalars the recompute needs.
+// Rows past the last active token are filled with zeros (g = 0, target = -1).
+// One workgroup per row.
+template <typename T_>
+__global__ void __launch_bounds__(256)
+gather_chunk_kernel(const T_ *__restrict__ X, int64_t H, const int32_t *__restrict__ act_idx,
+                    const int32_t *__restrict__ n_act, int64_t row_base, int64_t rows,
+                    const int32_t *__restrict__ target, const float *__restrict__ lse, const float *__restrict__ g,
+                    T_ *__restrict__ Xc, int32_t *__restrict__ tgt_c, float *__restrict__ lse_c,
+                    float *__restrict__ g_c) {
+    const int64_t r = blockIdx.x;
+    const bool live = r < active_rows(n_act, row_base, rows);
+    const int64_t src = live ? act_idx[row_base + r] : 0;
+    const int n16 = static_cast<int>(H * sizeof(T_) / 16);  // H is a multiple of 64
+    const uint4 *in = reinterpret_cast<const uint4 *>(X + src * H);
+    uint4 *out = reinterpret_cast<uint4 *>(Xc + r * H);
+    for (int i = threadIdx.x; i < n16; i += 256) out[i] = live ? in[i] : make_uint4(0u, 0u, 0u, 0u);
+    if (threadIdx.x == 0) {
+        tgt_c[r] = live ? target[src] : -1;
+        lse_c[r] = live ? lse[src] : 0.0f;
+        g_c[r] = live ? g[src] : 0.0f;
+    }
+}
+
+// ----------------------------------------------------------------------------
 // forward: vocabulary sweep with online log-sum-exp and target capture
 // ----------------------------------------------------------------------------
 // Tile rows (m) are vocabulary entries, tile columns (n) are tokens, so that each
@@ -199,17 +280,21 @@ fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const
 // dz[t][v] = g[t] * ([v == target[t]] - exp(z[t][v] - lse[t])), written both as
 // dZ[t][v] (row stride ldz, vocabulary contiguous: operand of dHidden) and as
 // dZT[v][t] (row stride ldzt, tokens contiguous: operand of dW).  Columns
-// V <= v < V_pad of dZ and tokens past T_valid are written as zeros.
+// V <= v < V_pad of dZ and tokens past T_valid are written as zeros.  Token tiles
+// that start at or after the number of active rows of this chunk (device value
+// n_act[0] - row_base) are skipped altogether.
 __global__ void __launch_bounds__(TL::NT)
 recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, int64_t V_pad,
                     const char *__restrict__ X, int64_t ldx_bytes, int64_t T_valid, int KT,
                     const int32_t *__restrict__ target, const float *__restrict__ lse,
                     const float *__restrict__ g, int64_t nVt, int64_t nTt, bf16_t *__restrict__ dZ,
-                    int64_t ldz, bf16_t *__restrict__ dZT, int64_t ldzt) {
+                    int64_t ldz, bf16_t *__restrict__ dZT, int64_t ldzt, const int32_t *__restrict__ n_act,
+                    int64_t row_base) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     int64_t tm, tn;
     if (!TileOrder(nVt, nTt).tile(blockIdx.x, tm, tn)) return;
     const int64_t m0 = tm * TL::BM, n0 = tn * TL::BN;
+    if (n0 >= active_rows(n_act, row_base, T_valid)) return;  // token tiles past the last active token
     TL::Acc acc;
     TL::zero(acc);
     TL::mainloop(W, ldw_bytes, m0, V, X, ldx_bytes, n0, T_valid, KT, lds, acc);
@@ -308,18 +393,36 @@ recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, in
 // ----------------------------------------------------------------------------
 // backward, steps 2 and 3: plain contraction with a store / accumulate epilogue
 // ----------------------------------------------------------------------------
-// out[m*ldo + n] (=|+=) sum_k A[m][k] B[n][k]
+// out[row(m)*ldo + n] (=|+=) sum_k A[m][k] B[n][k]
+// With n_act != NULL the extent that holds active tokens is read on the device
+// (rows = active_rows(n_act, row_base, .)): limit == kLimitRows keeps only the first
+// `rows` rows of A and stores row m at out row row_map[m] (dHidden: scatter back to the
+// tokens' own rows); limit == kLimitK contracts only over the first `rows` values of
+// the contraction index, rounded up to whole tiles of tokens (dW).
+constexpr int kLimitRows = 1, kLimitK = 2;
+
 __global__ void __launch_bounds__(TL::NT)
 gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, const char *__restrict__ B,
                   int64_t ldb_bytes, int64_t N, int KT, void *__restrict__ out, int64_t ldo, int out_dtype,
-                  int accumulate) {
+                  int accumulate, const int32_t *__restrict__ n_act, int64_t row_base, int limit,
+                  const int32_t *__restrict__ row_map) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     int64_t tm, tn;
     if (!TileOrder(ceil_div(M, TL::BM), ceil_div(N, TL::BN)).tile(blockIdx.x, tm, tn)) return;
     const int64_t m0 = tm * TL::BM, n0 = tn * TL::BN;
+    int64_t m_end = M;
+    if (n_act && limit == kLimitRows) {
+        m_end = active_rows(n_act, row_base, M);
+        if (m0 >= m_end) return;
+    }
+    if (n_act && limit == kLimitK) {
+        const int64_t k_rows = active_rows(n_act, row_base, static_cast<int64_t>(KT) * kBK);
+        KT = __builtin_amdgcn_readfirstlane(static_cast<int>(ceil_div(k_rows, TL::BN) * (TL::BN / kBK)));
+        if (KT == 0 && accumulate) return;  // nothing to add
+    }
     TL::Acc acc;
     TL::zero(acc);
-    TL::mainloop(A, lda_bytes, m0, M, B, ldb_bytes, n0, N, KT, lds, acc);
+    if (KT > 0) TL::mainloop(A, lda_bytes, m0, M, B, ldb_bytes, n0, N, KT, lds, acc);
 #pragma unroll
     for (int fn = 0; fn < TL::FN; ++fn) {
         const int64_t n = n0 + TL::acc_col(fn);
@@ -328,8 +431,9 @@ gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, cons
         for (int fm = 0; fm < TL::FM; ++fm)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int64_t m = m0 + TL::acc_row(fm, r);
-                if (m >= M) continue;
+                int64_t m = m0 + TL::acc_row(fm, r);
+                if (m >= m_end) continue;
+                if (row_map) m = row_map[m];
                 if (out_dtype == SPO_FP32) {
                     float *o = static_cast<float *>(out) + m * ldo + n;
                     *o = accumulate ? *o + acc[fm][fn][r] : acc[fm][fn][r];
@@ -452,6 +556,9 @@ struct BwdPlan {
     double *count;
     float *g, *dW_acc;
     bf16_t *WT, *XT, *dZ, *dZT, *Xs, *Ws, *Wvh;
+    int32_t *act_idx, *n_act, *tgt_c;  // active-token list, its length, per-chunk compact copies
+    float *lse_c, *g_c;
+    void *Xc;
     size_t bytes;
 };
 
@@ -467,6 +574,12 @@ static BwdPlan plan_bwd(const spo_pg_desc *d, int64_t chunk_tokens, void *ws, bo
     Arena a(ws);
     p.count = a.take<double>(1);
     p.g = a.take<float>(p.T_pad);
+    p.act_idx = a.take<int32_t>(p.T_pad);
+    p.n_act = a.take<int32_t>(1);
+    p.tgt_c = a.take<int32_t>(p.Tc);
+    p.lse_c = a.take<float>(p.Tc);
+    p.g_c = a.take<float>(p.Tc);
+    p.Xc = a.take<char>(static_cast<size_t>(p.Tc) * d->H * (d->dtype == SPO_FP32 ? 4 : 2));
     p.WT = a.take<bf16_t>(static_cast<size_t>(d->H) * p.V_pad);
     p.XT = a.take<bf16_t>(static_cast<size_t>(d->H) * p.ldt);
     p.dZ = a.take<bf16_t>(static_cast<size_t>(p.Tc) * p.V_pad);
@@ -498,11 +611,12 @@ static void launch_transpose(const SrcT *src, int64_t R, int64_t C, int64_t ld_s
 }
 
 static void launch_gemm(const bf16_t *A, int64_t lda, int64_t M, const bf16_t *B, int64_t ldb, int64_t N, int64_t K,
-                        void *out, int64_t ldo, int out_dtype, int accumulate, hipStream_t s) {
+                        void *out, int64_t ldo, int out_dtype, int accumulate, const int32_t *n_act, int64_t row_base,
+                        int limit, const int32_t *row_map, hipStream_t s) {
     const TileOrder ord(ceil_div(M, TL::BM), ceil_div(N, TL::BN));
     gemm_store_kernel<<<static_cast<unsigned>(ord.blocks()), TL::NT, TL::LDS_BYTES, s>>>(
         reinterpret_cast<const char *>(A), lda * 2, M, reinterpret_cast<const char *>(B), ldb * 2, N,
-        static_cast<int>(K / kBK), out, ldo, out_dtype, accumulate);
+        static_cast<int>(K / kBK), out, ldo, out_dtype, accumulate, n_act, row_base, limit, row_map);
 }
 
 int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float grad_loss, void *d_hidden,
@@ -543,40 +657,54 @@ int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float g
         Wk = Wvh;
         if (d_hidden) launch_transpose(Wvh, V, H, H, p.WT, p.V_pad, H, p.V_pad, s);
     }
+    // the tokens that carry a gradient, in order; the chunks below run over this list
+    compact_active_kernel<<<1, 1024, 0, s>>>(p.g, T, p.act_idx, p.n_act);
+    if (d_hidden) {  // rows of the other tokens stay zero
+        const int64_t words = T * H / (d_hidden_dtype == SPO_FP32 ? 1 : 2);
+        fill_zero_kernel<<<grid1(words), 256, 0, s>>>(static_cast<uint32_t *>(d_hidden), words);
+    }
     const int64_t nVt = ceil_div(V, TL::BM);
     for (int64_t t0 = 0, c = 0; t0 < T; t0 += p.Tc, ++c) {
-        const int64_t Tv = std::min(p.Tc, T - t0), Tcp = round_up(Tv, TL::BN);
+        // rows [t0, t0 + Tcp) of the compact order; how many of them exist is known on the
+        // device only, so every launch is sized for the most there can be and trims itself
+        const int64_t Tcp = round_up(std::min(p.Tc, T - t0), TL::BN);
         const bf16_t *Xk;
         if (d->dtype == SPO_FP32) {
-            const float *xs = static_cast<const float *>(d->hidden) + t0 * H;
-            split_expand_kernel<<<grid1(Tv * H), 256, 0, s>>>(xs, Tv, H, p.Xs, 1);
+            float *xc = static_cast<float *>(p.Xc);
+            gather_chunk_kernel<float><<<static_cast<unsigned>(Tcp), 256, 0, s>>>(
+                static_cast<const float *>(d->hidden), H, p.act_idx, p.n_act, t0, Tcp, d->target, lse, p.g, xc,
+                p.tgt_c, p.lse_c, p.g_c);
+            split_expand_kernel<<<grid1(Tcp * H), 256, 0, s>>>(xc, Tcp, H, p.Xs, 1);
             Xk = p.Xs;
-            if (d_W) launch_transpose(xs, Tv, H, H, p.XT, Tcp, H, p.ldt, s);
+            if (d_W) launch_transpose(xc, Tcp, H, H, p.XT, Tcp, H, p.ldt, s);
         } else {
-            const bf16_t *xs = static_cast<const bf16_t *>(d->hidden) + t0 * H;
-            Xk = xs;
-            if (d_W) launch_transpose(xs, Tv, H, H, p.XT, Tcp, H, p.ldt, s);
+            bf16_t *xc = static_cast<bf16_t *>(p.Xc);
+            gather_chunk_kernel<bf16_t><<<static_cast<unsigned>(Tcp), 256, 0, s>>>(
+                static_cast<const bf16_t *>(d->hidden), H, p.act_idx, p.n_act, t0, Tcp, d->target, lse, p.g, xc,
+                p.tgt_c, p.lse_c, p.g_c);
+            Xk = xc;
+            if (d_W) launch_transpose(xc, Tcp, H, H, p.XT, Tcp, H, p.ldt, s);
         }
         {
             const TileOrder ord(nVt, Tcp / TL::BN);
             ScopedKernelTimer timer(kTimeRecompute, s);
             recompute_dz_kernel<<<static_cast<unsigned>(ord.blocks()), TL::NT, TL::LDS_BYTES, s>>>(
                 reinterpret_cast<const char *>(Wk), p.Kc * 2, V, p.V_pad, reinterpret_cast<const char *>(Xk), p.Kc * 2,
-                Tv, static_cast<int>(p.Kc / kBK), d->target + t0, lse + t0, p.g + t0, nVt, Tcp / TL::BN,
-                d_hidden ? p.dZ : nullptr, p.V_pad, d_W ? p.dZT : nullptr, p.ldt);
+                Tcp, static_cast<int>(p.Kc / kBK), p.tgt_c, p.lse_c, p.g_c, nVt, Tcp / TL::BN,
+                d_hidden ? p.dZ : nullptr, p.V_pad, d_W ? p.dZT : nullptr, p.ldt, p.n_act, t0);
         }
         if (d_hidden) {
             ScopedKernelTimer timer(kTimeDHidden, s);
-            char *dx = static_cast<char *>(d_hidden) + t0 * H * (d_hidden_dtype == SPO_FP32 ? 4 : 2);
-            launch_gemm(p.dZ, p.V_pad, Tv, p.WT, p.V_pad, H, p.V_pad, dx, H, d_hidden_dtype, 0, s);
+            launch_gemm(p.dZ, p.V_pad, Tcp, p.WT, p.V_pad, H, p.V_pad, d_hidden, H, d_hidden_dtype, 0, p.n_act, t0,
+                        kLimitRows, p.act_idx + t0, s);
         }
         if (d_W) {
             const int acc = (c > 0 || accumulate_dW) ? 1 : 0;
             ScopedKernelTimer timer(kTimeDW, s);
             if (d->w_layout == SPO_W_VH)
-                launch_gemm(p.dZT, p.ldt, V, p.XT, p.ldt, H, Tcp, dW32, H, SPO_FP32, acc, s);
+                launch_gemm(p.dZT, p.ldt, V, p.XT, p.ldt, H, Tcp, dW32, H, SPO_FP32, acc, p.n_act, t0, kLimitK, nullptr, s);
             else
-                launch_gemm(p.XT, p.ldt, H, p.dZT, p.ldt, V, Tcp, dW32, V, SPO_FP32, acc, s);
+                launch_gemm(p.XT, p.ldt, H, p.dZT, p.ldt, V, Tcp, dW32, V, SPO_FP32, acc, p.n_act, t0, kLimitK, nullptr, s);
         }
     }
     if (need_acc) f32_to_bf16_kernel<<<grid1(V * H), 256, 0, s>>>(p.dW_acc, static_cast<bf16_t *>(d_W), V * H);

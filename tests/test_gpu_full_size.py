@@ -127,14 +127,14 @@ def _run_full(spo, oracle, name, n_rows, n_dw_tokens, n_vsel):
 
 @pytest.mark.timeout(600)
 def test_small_model_shape_c2(spo, oracle):
-    _run_full(spo, oracle, "C2", n_rows=96, n_dw_tokens=160, n_vsel=48)
+    _run_full(spo, oracle, "C2", n_rows=256, n_dw_tokens=160, n_vsel=64)
 
 
 @pytest.mark.timeout(900)
 def test_qwen3_8b_head_shape_c3(spo, oracle):
-    _run_full(spo, oracle, "C3", n_rows=96, n_dw_tokens=160, n_vsel=48)
+    _run_full(spo, oracle, "C3", n_rows=1024, n_dw_tokens=256, n_vsel=64)
 
 
 @pytest.mark.timeout(900)
 def test_long_horizon_masked_shape_c4(spo, oracle):
-    _run_full(spo, oracle, "C4", n_rows=64, n_dw_tokens=96, n_vsel=32)
+    _run_full(spo, oracle, "C4", n_rows=256, n_dw_tokens=128, n_vsel=64)
