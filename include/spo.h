@@ -226,7 +226,11 @@ int spo_pg_loss_fwd(const spo_pg_desc *d, float *loss, float *logp, float *lse, 
  * chunk_tokens  tokens whose logit gradients are held in the workspace at once
  *               (0 picks a default).  The backward recomputes the logits tile by
  *               tile; a chunk's bf16 logit gradients live in the workspace
- *               between the three contractions, never the full [T x V]. */
+ *               between the three contractions, never the full [T x V].
+ * Tokens whose gradient factor is zero (masked, on the clipped branch, or in a
+ * response with zero advantage) are left out of the recompute and of both
+ * contractions: the cost of the backward follows the number of remaining tokens,
+ * and their rows of d_hidden are exact zeros. */
 size_t spo_pg_loss_bwd_workspace_bytes(const spo_pg_desc *d, int64_t chunk_tokens);
 int spo_pg_loss_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float grad_loss,
                     void *d_hidden, int d_hidden_dtype, void *d_W, int d_W_dtype,
