@@ -98,6 +98,29 @@ def test_backward_chunks_and_output_dtypes(spo, oracle):
     assert rel_l2(f64(dx3), rb["d_hidden"]) < GRAD_TOL and rel_l2(f64(dw3), rb["d_W"]) < GRAD_TOL
 
 
+@pytest.mark.parametrize("keep,chunk", [(256, 256), (257, 256), (1, 0), (300, 512), (511, 256)])
+def test_backward_runs_over_active_tokens_only(spo, oracle, keep, chunk):
+    # A sparse loss mask: the backward gathers the tokens that carry a gradient and works on
+    # that list, `keep` of them here, chosen to end exactly on, one past, and far from the
+    # boundaries of token tiles and chunks.  Rows of all other tokens must be exact zeros.
+    say(f"fused bf16 mid, {keep} unmasked tokens, chunk_tokens={chunk}")
+    case = Case(MID, MID_LENGTHS)
+    case.set_old_from_oracle(oracle)
+    rng = np.random.default_rng(keep)
+    live = np.sort(rng.choice(case.T, keep, replace=False))
+    case.mask = np.zeros(case.T, np.uint8)
+    case.mask[live] = 1
+    fwd, dx, dw = run_fwd_bwd(spo, case, chunk_tokens=chunk)
+    check_forward(case, oracle, fwd)
+    rb = oracle.pg_loss_bwd(*case.oracle_inputs(), *case.eps)
+    assert rel_l2(f64(dx), rb["d_hidden"]) < GRAD_TOL and rel_l2(f64(dw), rb["d_W"]) < GRAD_TOL
+    dead = np.setdiff1d(np.arange(case.T), live)
+    assert not dx[torch.as_tensor(dead, device="cuda")].any()
+    # a clipped token is dropped from the list like a masked one
+    zero_rows = np.flatnonzero(~rb["d_hidden"].any(axis=1))
+    assert not dx[torch.as_tensor(zero_rows, device="cuda")].any()
+
+
 def test_results_are_bitwise_reproducible(spo, oracle):
     say("fused bf16 mid, determinism")
     case = Case(MID, MID_LENGTHS)
