@@ -75,7 +75,9 @@ const char *spo_status_string(int status);
  * idx_out       [B] int32.
  * info          optional int32[2]: info[0] = 0, or 1 if some slot ran out of
  *               attempts (its idx_out entries are then -1); info[1] = largest
- *               attempt number used.
+ *               attempt number used.  If every weight is zero (eps_explore = 0
+ *               and every v_i is 0 or 1) nothing can be drawn: all entries are
+ *               -1 and info[0] = 1.
  * max_attempts  bound on attempts per slot (0 selects 2^20).
  * ws            spo_sample_prompts_workspace_bytes(N, B) bytes, 256-byte aligned.
  * Limits: 1 <= N < 2^31, 1 <= B <= 16384 (replace = 0) or B < 2^31 (replace = 1).

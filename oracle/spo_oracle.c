@@ -256,6 +256,10 @@ int spo_oracle_sample(const float *alpha, const float *beta, int64_t N, int32_t 
     }
     uint64_t total = run;
     int rc = 0;
+    if (total == 0) { /* every weight is zero: nothing can be drawn */
+        for (int32_t k = 0; k < B; ++k) idx_out[k] = -1;
+        rc = -1;
+    }
     for (int32_t k = 0; k < B && rc == 0; ++k) {
         uint32_t a = 0;
         for (;;) {

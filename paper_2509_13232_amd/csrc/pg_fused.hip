@@ -447,21 +447,18 @@ gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, cons
 // ----------------------------------------------------------------------------
 // host side
 // ----------------------------------------------------------------------------
+// The kernels use more dynamic LDS than the default limit allows.  The attribute belongs
+// to the current device's copy of the kernel, so it is set on every call (a host-side
+// table lookup) rather than remembered in a process-wide flag.
 static int set_lds_limit() {
-    static bool done = false;
-    static int status = SPO_OK;
-    if (!done) {
-        hipError_t e = hipSuccess;
-        e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_sweep_kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
-        e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(recompute_dz_kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
-        e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_store_kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
-        status = e == hipSuccess ? SPO_OK : SPO_EHIP;
-        done = true;
-    }
-    return status;
+    hipError_t e = hipSuccess;
+    e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_sweep_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
+    e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(recompute_dz_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
+    e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_store_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
+    return e == hipSuccess ? SPO_OK : SPO_EHIP;
 }
 
 static inline int64_t round_up(int64_t x, int64_t a) { return ceil_div(x, a) * a; }

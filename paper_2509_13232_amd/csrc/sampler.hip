@@ -137,8 +137,9 @@ draw_with_replacement_kernel(const uint64_t *__restrict__ cdf, int64_t N, const 
                              uint64_t seed, uint64_t iteration, int B, int32_t *__restrict__ idx_out,
                              int32_t *__restrict__ info) {
     const int k = blockIdx.x * blockDim.x + threadIdx.x;
-    if (k < B) idx_out[k] = draw_index(cdf, N, *total, seed, iteration, k, 0);
-    if (info && k == 0) { info[0] = 0; info[1] = 0; }
+    const uint64_t tot = *total;  // zero: every weight is zero, nothing can be drawn
+    if (k < B) idx_out[k] = tot ? draw_index(cdf, N, tot, seed, iteration, k, 0) : -1;
+    if (info && k == 0) { info[0] = tot ? 0 : 1; info[1] = 0; }
 }
 
 // Successive sampling without replacement as a fixed point: every slot starts at
@@ -156,6 +157,11 @@ draw_without_replacement_kernel(const uint64_t *__restrict__ cdf, int64_t N, con
     __shared__ int changed_flag[2];
     __shared__ int failed_flag;
     const uint64_t total = *total_p;
+    if (total == 0) {  // every weight is zero: nothing can be drawn (uniform exit, before any barrier)
+        for (int k = threadIdx.x; k < B; k += kResolveThreads) idx_out[k] = -1;
+        if (info && threadIdx.x == 0) { info[0] = 1; info[1] = 0; }
+        return;
+    }
     uint32_t attempt[kSlotsPerThread];
     bool dead[kSlotsPerThread];
 #pragma unroll
@@ -269,14 +275,11 @@ extern "C" int spo_sample_prompts(const float *alpha, const float *beta, int64_t
     if (replace) {
         draw_with_replacement_kernel<<<(B + 255) / 256, 256, 0, s>>>(w.cdf, N, w.total, seed, iteration, B, idx_out, info);
     } else {
-        static bool lds_limit_set = false;  // candidates of 16384 slots need the full 64 KiB plus the flags
-        if (!lds_limit_set) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(draw_without_replacement_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    kMaxSlotsNoReplace * static_cast<int>(sizeof(int32_t))) != hipSuccess)
-                return SPO_EHIP;
-            lds_limit_set = true;
-        }
+        // candidates of 16384 slots need the full 64 KiB; the attribute is per device, set on every call
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(draw_without_replacement_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                kMaxSlotsNoReplace * static_cast<int>(sizeof(int32_t))) != hipSuccess)
+            return SPO_EHIP;
         draw_without_replacement_kernel<<<1, kResolveThreads, static_cast<size_t>(B) * sizeof(int32_t), s>>>(
             w.cdf, N, w.total, seed, iteration, B, max_attempts, idx_out, info);
     }

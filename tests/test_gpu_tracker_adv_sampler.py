@@ -172,6 +172,19 @@ def test_sampler_reports_exhausted_attempts(spo, oracle):
     assert len(set(alive.tolist())) == len(alive)
 
 
+@pytest.mark.parametrize("replace", [True, False])
+def test_sampler_with_all_weights_zero(spo, oracle, replace):
+    # no exploration bonus and every estimate at 0 or 1: every weight is zero
+    say(f"sample_prompts total weight zero, replace={replace}")
+    a = np.array([0.0, 3.0, 0.0, 1.0], np.float32)
+    b = np.array([2.0, 0.0, 5.0, 0.0], np.float32)
+    with pytest.raises(RuntimeError):
+        oracle.sample_prompts(a, b, 3, 0.0, 1, 2, replace)
+    gidx, info = spo.spo_sample_prompts(dev(a), dev(b), 3, 0.0, 1, 2, replace, return_info=True)
+    torch.cuda.synchronize()
+    assert (gidx.cpu().numpy() == -1).all() and info.cpu().numpy()[0] == 1
+
+
 def test_sampler_after_update_sees_new_state(spo, oracle):
     # the order of the training loop: sample -> advantages (pre-update) -> update
     cfg = wl.CONFIGS["C2"]

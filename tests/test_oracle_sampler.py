@@ -145,3 +145,16 @@ def test_without_replacement_distinct_and_permutation(oracle):
     assert np.array_equal(d0, oracle.sample_prompts(al, be, 128, 0.05, 7, 0))
     with pytest.raises(ValueError):
         oracle.sample_prompts(a, a, N + 1, 0.05, 0, 0, replace=False)
+
+
+def test_zero_total_weight_draws_nothing(oracle):
+    # eps = 0 and every estimate at 0 or 1: all weights vanish; the sampler must refuse, not index past the end
+    a = np.array([0.0, 3.0, 0.0, 1.0], np.float32)
+    b = np.array([2.0, 0.0, 5.0, 0.0], np.float32)
+    assert not oracle.weights(a, b, 0.0).any()
+    for replace in (True, False):
+        with pytest.raises(RuntimeError):
+            oracle.sample_prompts(a, b, 2, 0.0, 0, 0, replace)
+    # a single entry with weight keeps everything on it (with replacement)
+    a[0], b[0] = 1.0, 1.0
+    assert (oracle.sample_prompts(a, b, 5, 0.0, 0, 0, True) == 0).all()
