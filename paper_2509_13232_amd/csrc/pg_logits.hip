@@ -70,19 +70,24 @@ logits_row_lse_kernel(const T *__restrict__ logits, int64_t V, const int32_t *__
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 if (v0 + u * step < V) Vec<T>::load(row + v0 + u * step, x[u]);
+            // one new maximum and one rescaling of the running sum for the whole group of loads
+            float mx = m;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (v0 + u * step >= V) break;
-                float mx = x[u][0];
 #pragma unroll
-                for (int i = 1; i < N; ++i) mx = fmaxf(mx, x[u][i]);
-                const float nm = fmaxf(m, mx), nm2 = -nm * kLog2e;
-                float a = 0.0f;
+                for (int i = 0; i < N; ++i) mx = fmaxf(mx, x[u][i]);
+            }
+            const float nm2 = -mx * kLog2e;
+            float a = 0.0f;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (v0 + u * step >= V) break;
 #pragma unroll
                 for (int i = 0; i < N; ++i) a += __builtin_amdgcn_exp2f(fmaf(x[u][i], kLog2e, nm2));
-                s = s * __builtin_amdgcn_exp2f((m - nm) * kLog2e) + a;
-                m = nm;
             }
+            s = s * __builtin_amdgcn_exp2f((m - mx) * kLog2e) + a;
+            m = mx;
         }
     } else {
         for (int64_t v = threadIdx.x; v < V; v += kRowThreads) lse_merge(m, s, Vec<T>::get(row + v), 1.0f);
