@@ -46,6 +46,7 @@ def main() -> int:
     ap.add_argument("--chunk-tokens", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-logits-in", action="store_true")
+    ap.add_argument("--no-small", action="store_true", help="skip the tracker / advantage / sampler timings")
     ap.add_argument("--cpu-tokens", type=int, default=128)
     ap.add_argument("--calibrate-copy", action="store_true")
     args = ap.parse_args()
@@ -211,6 +212,42 @@ def main() -> int:
                             "bwd_frac_hbm": round(bwd_gbps / PEAK_HBM_GBPS, 4),
                             "tokens_per_s_fwd_bwd": round(Tl / ((fwd_ms + bwd_ms) * 1e-3), 1)}
         del logits, dl
+
+    # ---------------------------------------------------------------- tracker / advantage / sampler at 2^20 prompts
+    if not args.no_small:
+        c5 = wl.CONFIGS["C5"]
+        a5, b5 = wl.tracker_state(c5)
+        a5, b5 = torch.as_tensor(a5).to(dev), torch.as_tensor(b5).to(dev)
+        i5 = wl.distinct_indices(c5, c5.B)
+        r5 = torch.as_tensor(wl.rewards(c5, i5)).to(dev)
+        k5 = torch.as_tensor(wl.kl_divergences(c5, c5.B)).to(dev)
+        i5 = torch.as_tensor(i5).to(dev)
+        ws5 = torch.empty(spo.lib().spo_sample_prompts_workspace_bytes(c5.N, c5.B), dtype=torch.uint8, device=dev)
+
+        def timed(fn, reps=20):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps * 1e3   # microseconds per call, launch overhead included
+
+        us_sample = timed(lambda: spo.spo_sample_prompts(a5, b5, c5.B, c5.eps_explore, c5.sample_seed, 1, workspace=ws5))
+        us_sample_r = timed(lambda: spo.spo_sample_prompts(a5, b5, c5.B, c5.eps_explore, c5.sample_seed, 1, True,
+                                                           workspace=ws5))
+        us_adv = timed(lambda: spo.spo_advantages(a5, b5, i5, r5))
+        us_upd = timed(lambda: spo.spo_tracker_update(a5, b5, i5, r5, k5, c5.d_half, c5.rho_min, c5.rho_max))
+        scan_bytes = c5.N * (8 + 8 + 8)   # alpha, beta read in two passes (8 B each), 8-byte CDF written
+        out["small_kernels"] = {
+            "workload": f"C5: {c5.N} tracked prompts, batch {c5.B}",
+            "sample_without_replacement_us": round(us_sample, 1), "sample_with_replacement_us": round(us_sample_r, 1),
+            "advantages_us": round(us_adv, 1), "tracker_update_us": round(us_upd, 1),
+            "weight_scan_GBps": round(scan_bytes / (us_sample_r * 1e-6) / 1e9, 1),
+            "note": "host-visible time per call on the launch stream (several small launches each); "
+                    "weight_scan_GBps counts 24 B per prompt over the with-replacement call"}
 
     # ---------------------------------------------------------------- the oracle on the host cores
     if not args.no_cpu_baseline:

@@ -149,11 +149,25 @@ draw_with_replacement_kernel(const uint64_t *__restrict__ cdf, int64_t N, const 
 // fixed point is the sequential definition "first attempt not taken by an
 // earlier slot".  One workgroup; the loop ends because every sweep that does not
 // end it raises some attempt counter and counters are capped by max_attempts.
+//
+// "Held by a lower slot" is decided through owner[N] (all kNoOwner on entry and
+// again on exit): every live slot files its number under its candidate with an
+// atomic minimum, then reads the minimum back.  The minimum does not depend on
+// the order of the atomics, so the result is the same on every run.  The owner
+// entries are read and cleared with L2-coherent accesses: the atomics act at the
+// L2, a plain load could be served from the CU's own cache.
+constexpr int32_t kNoOwner = 0x7fffffff;
+
+__global__ void __launch_bounds__(256) fill_owner_kernel(int32_t *__restrict__ owner, int64_t N) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i < N) owner[i] = kNoOwner;
+}
+
 __global__ void __launch_bounds__(kResolveThreads)
 draw_without_replacement_kernel(const uint64_t *__restrict__ cdf, int64_t N, const uint64_t *__restrict__ total_p,
                                 uint64_t seed, uint64_t iteration, int B, uint32_t max_attempts,
-                                int32_t *__restrict__ idx_out, int32_t *__restrict__ info) {
-    extern __shared__ int32_t cand[];  // B candidates
+                                int32_t *__restrict__ idx_out, int32_t *__restrict__ info,
+                                int32_t *__restrict__ owner) {
     __shared__ int changed_flag[2];
     __shared__ int failed_flag;
     const uint64_t total = *total_p;
@@ -163,47 +177,50 @@ draw_without_replacement_kernel(const uint64_t *__restrict__ cdf, int64_t N, con
         return;
     }
     uint32_t attempt[kSlotsPerThread];
-    bool dead[kSlotsPerThread];
+    int32_t cand[kSlotsPerThread];
+    bool live[kSlotsPerThread];   // slot exists and has not run out of attempts
 #pragma unroll
     for (int s = 0; s < kSlotsPerThread; ++s) {
         attempt[s] = 0;
-        dead[s] = false;
         const int k = s * kResolveThreads + threadIdx.x;
-        if (k < B) cand[k] = draw_index(cdf, N, total, seed, iteration, k, 0);
+        live[s] = k < B;
+        cand[s] = live[s] ? draw_index(cdf, N, total, seed, iteration, k, 0) : -1;
     }
     if (threadIdx.x == 0) { changed_flag[0] = 0; changed_flag[1] = 0; failed_flag = 0; }
     __syncthreads();
     for (int sweep = 0;; ++sweep) {
+#pragma unroll
+        for (int s = 0; s < kSlotsPerThread; ++s)
+            if (live[s]) atomicMin(&owner[cand[s]], s * kResolveThreads + static_cast<int>(threadIdx.x));
+        __threadfence();
+        __syncthreads();  // every claim of this sweep is filed
         bool conflict[kSlotsPerThread];
 #pragma unroll
-        for (int s = 0; s < kSlotsPerThread; ++s) {
-            const int k = s * kResolveThreads + threadIdx.x;
-            conflict[s] = false;
-            if (k < B && !dead[s]) {
-                const int32_t mine = cand[k];
-                for (int j = 0; j < k; ++j)
-                    if (cand[j] == mine) { conflict[s] = true; break; }
-            }
-        }
-        __syncthreads();  // all reads of this sweep are done
+        for (int s = 0; s < kSlotsPerThread; ++s)
+            conflict[s] = live[s] && __hip_atomic_load(&owner[cand[s]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) <
+                                         s * kResolveThreads + static_cast<int>(threadIdx.x);
+        __syncthreads();  // every claim has been read
+#pragma unroll
+        for (int s = 0; s < kSlotsPerThread; ++s)
+            if (live[s]) __hip_atomic_store(&owner[cand[s]], kNoOwner, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         bool any = false;
 #pragma unroll
         for (int s = 0; s < kSlotsPerThread; ++s) {
-            const int k = s * kResolveThreads + threadIdx.x;
             if (conflict[s]) {
                 any = true;
                 if (++attempt[s] >= max_attempts) {
-                    dead[s] = true;
-                    cand[k] = -1 - k;  // unique, never collides
+                    live[s] = false;
+                    cand[s] = -1;
                     failed_flag = 1;
                 } else {
-                    cand[k] = draw_index(cdf, N, total, seed, iteration, k, attempt[s]);
+                    cand[s] = draw_index(cdf, N, total, seed, iteration, s * kResolveThreads + threadIdx.x, attempt[s]);
                 }
             }
         }
         int *flag = &changed_flag[sweep & 1];
         if (any) *flag = 1;
-        __syncthreads();
+        __threadfence();
+        __syncthreads();  // owner is clear again; the flag is complete
         const bool again = *flag != 0;
         if (threadIdx.x == 0) changed_flag[(sweep + 1) & 1] = 0;
         if (!again) break;
@@ -214,7 +231,7 @@ draw_without_replacement_kernel(const uint64_t *__restrict__ cdf, int64_t N, con
     for (int s = 0; s < kSlotsPerThread; ++s) {
         const int k = s * kResolveThreads + threadIdx.x;
         if (k < B) {
-            idx_out[k] = dead[s] ? -1 : cand[k];
+            idx_out[k] = cand[s];   // -1 for a slot that ran out of attempts
             amax = attempt[s] > amax ? attempt[s] : amax;
         }
     }
@@ -230,6 +247,7 @@ draw_without_replacement_kernel(const uint64_t *__restrict__ cdf, int64_t N, con
 
 struct SamplerWorkspace {
     uint64_t *cdf, *block_sums, *total;
+    int32_t *owner;
     size_t bytes;
 };
 
@@ -239,6 +257,7 @@ static SamplerWorkspace sampler_layout(void *ws, int64_t N) {
     w.cdf = a.take<uint64_t>(static_cast<size_t>(N));
     w.block_sums = a.take<uint64_t>(static_cast<size_t>(ceil_div(N, kScanItems)));
     w.total = a.take<uint64_t>(1);
+    w.owner = a.take<int32_t>(static_cast<size_t>(N));
     w.bytes = a.used;
     return w;
 }
@@ -275,13 +294,9 @@ extern "C" int spo_sample_prompts(const float *alpha, const float *beta, int64_t
     if (replace) {
         draw_with_replacement_kernel<<<(B + 255) / 256, 256, 0, s>>>(w.cdf, N, w.total, seed, iteration, B, idx_out, info);
     } else {
-        // candidates of 16384 slots need the full 64 KiB; the attribute is per device, set on every call
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(draw_without_replacement_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize,
-                                kMaxSlotsNoReplace * static_cast<int>(sizeof(int32_t))) != hipSuccess)
-            return SPO_EHIP;
-        draw_without_replacement_kernel<<<1, kResolveThreads, static_cast<size_t>(B) * sizeof(int32_t), s>>>(
-            w.cdf, N, w.total, seed, iteration, B, max_attempts, idx_out, info);
+        fill_owner_kernel<<<static_cast<unsigned>(ceil_div(N, 256)), 256, 0, s>>>(w.owner, N);
+        draw_without_replacement_kernel<<<1, kResolveThreads, 0, s>>>(w.cdf, N, w.total, seed, iteration, B, max_attempts,
+                                                                     idx_out, info, w.owner);
     }
     return launch_status();
 }
