@@ -312,6 +312,7 @@ recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, in
     // wavefront would scatter 64 pieces of 8 bytes over 64 rows per instruction.  The tile
     // is laid out as 256 token rows of 512 bytes, 16-byte chunk c of row t at position
     // c ^ (t % 32) (conflict-free both for the writes below and the row reads after).
+    static_assert(TL::LDS_BYTES >= TL::BN * 512 && TL::BM * 2 == 512, "the tile of bf16 gradients fits the operand stages");
     const int lane = threadIdx.x & 63;
     const int quad_lane = threadIdx.x & 3;
     char *ztile = lds;
