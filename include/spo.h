@@ -211,7 +211,7 @@ typedef struct {
  *       minimum, mean ratio over unmasked tokens, sum_t mask_t*obj_t.
  * Reductions run in a fixed order: results are bitwise reproducible.
  * Requirements (fused form): H a multiple of 64, H <= 65536, pointers 16-byte
- * aligned; fp32 inputs need SPO_W_VH.  T = 0 is allowed (loss = 0, the per-token
+ * aligned.  T = 0 is allowed (loss = 0, the per-token
  * pointers may then be NULL). */
 size_t spo_pg_loss_fwd_workspace_bytes(const spo_pg_desc *d);
 int spo_pg_loss_fwd(const spo_pg_desc *d, float *loss, float *logp, float *lse, float *stats,

@@ -73,6 +73,19 @@ transpose_to_bf16_kernel(const SrcT *__restrict__ src, int64_t R, int64_t C, int
     }
 }
 
+// dst[c][r] = src[r][c] (fp32, R x C -> C x R), 64 x 64 tiles through LDS.
+__global__ void __launch_bounds__(256)
+transpose_f32_kernel(const float *__restrict__ src, int64_t R, int64_t C, float *__restrict__ dst) {
+    __shared__ float tile[64][65];
+    const int64_t r0 = static_cast<int64_t>(blockIdx.x) * 64, c0 = static_cast<int64_t>(blockIdx.y) * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int i = ty; i < 64; i += 4)
+        if (r0 + i < R && c0 + tx < C) tile[i][tx] = src[(r0 + i) * C + c0 + tx];
+    __syncthreads();
+    for (int i = ty; i < 64; i += 4)
+        if (c0 + i < C && r0 + tx < R) dst[(c0 + i) * R + r0 + tx] = tile[tx][i];
+}
+
 __global__ void __launch_bounds__(256)
 f32_to_bf16_kernel(const float *__restrict__ src, bf16_t *__restrict__ dst, int64_t n) {
     const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
@@ -473,6 +486,7 @@ struct FwdPlan {
     float *part_max, *part_sum, *z_target;
     FwdPartial *partials;
     bf16_t *Xs, *Ws, *Wvh;  // split-expanded operands (fp32), [V,H] copy (HV layout)
+    float *W32;             // [V,H] copy of an fp32 head given as [H,V]
     size_t bytes;
 };
 
@@ -491,9 +505,11 @@ static FwdPlan plan_fwd(const spo_pg_desc *d, void *ws) {
     p.z_target = a.take<float>(p.T_pad);
     p.partials = a.take<FwdPartial>(p.nblk_tok);
     p.Xs = p.Ws = p.Wvh = nullptr;
+    p.W32 = nullptr;
     if (d->dtype == SPO_FP32) {
         p.Xs = a.take<bf16_t>(static_cast<size_t>(std::max<int64_t>(d->T, 1)) * p.Kc);
         p.Ws = a.take<bf16_t>(static_cast<size_t>(d->V) * p.Kc);
+        if (d->w_layout == SPO_W_HV) p.W32 = a.take<float>(static_cast<size_t>(d->V) * d->H);
     } else if (d->w_layout == SPO_W_HV) {
         p.Wvh = a.take<bf16_t>(static_cast<size_t>(d->V) * d->H);
     }
@@ -502,7 +518,6 @@ static FwdPlan plan_fwd(const spo_pg_desc *d, void *ws) {
 }
 
 static int check_fused(const spo_pg_desc *d) {
-    if (d->dtype == SPO_FP32 && d->w_layout == SPO_W_HV) return SPO_EUNSUPPORTED;
     if (reinterpret_cast<uintptr_t>(d->hidden) % 16 || reinterpret_cast<uintptr_t>(d->W) % 16) return SPO_EINVAL;
     return SPO_OK;
 }
@@ -523,7 +538,12 @@ int fused_fwd(const spo_pg_desc *d, float *loss, float *logp, float *lse, float 
         const char *X, *W;
         if (d->dtype == SPO_FP32) {
             split_expand_kernel<<<grid1(d->T * d->H), 256, 0, s>>>(static_cast<const float *>(d->hidden), d->T, d->H, p.Xs, 1);
-            split_expand_kernel<<<grid1(d->V * d->H), 256, 0, s>>>(static_cast<const float *>(d->W), d->V, d->H, p.Ws, 0);
+            const float *w32 = static_cast<const float *>(d->W);
+            if (d->w_layout == SPO_W_HV) {
+                transpose_f32_kernel<<<dim3(grid1(d->H, 64), grid1(d->V, 64)), 256, 0, s>>>(w32, d->H, d->V, p.W32);
+                w32 = p.W32;
+            }
+            split_expand_kernel<<<grid1(d->V * d->H), 256, 0, s>>>(w32, d->V, d->H, p.Ws, 0);
             X = reinterpret_cast<const char *>(p.Xs);
             W = reinterpret_cast<const char *>(p.Ws);
         } else {
@@ -554,6 +574,7 @@ struct BwdPlan {
     double *count;
     float *g, *dW_acc;
     bf16_t *WT, *XT, *dZ, *dZT, *Xs, *Ws, *Wvh;
+    float *W32;  // [V,H] copy of an fp32 head given as [H,V]
     int32_t *act_idx, *n_act, *tgt_c;  // active-token list, its length, per-chunk compact copies
     float *lse_c, *g_c;
     void *Xc;
@@ -584,9 +605,11 @@ static BwdPlan plan_bwd(const spo_pg_desc *d, int64_t chunk_tokens, void *ws, bo
     p.dZT = a.take<bf16_t>(static_cast<size_t>(d->V) * p.ldt);
     p.Xs = p.Ws = p.Wvh = nullptr;
     p.dW_acc = nullptr;
+    p.W32 = nullptr;
     if (d->dtype == SPO_FP32) {
         p.Xs = a.take<bf16_t>(static_cast<size_t>(p.Tc) * p.Kc);
         p.Ws = a.take<bf16_t>(static_cast<size_t>(d->V) * p.Kc);
+        if (d->w_layout == SPO_W_HV) p.W32 = a.take<float>(static_cast<size_t>(d->V) * d->H);
     } else if (d->w_layout == SPO_W_HV) {
         p.Wvh = a.take<bf16_t>(static_cast<size_t>(d->V) * d->H);
     }
@@ -643,9 +666,14 @@ int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float g
     // vocabulary-major head for the recompute, hidden-major head for dHidden
     const bf16_t *Wk;
     if (d->dtype == SPO_FP32) {
-        split_expand_kernel<<<grid1(V * H), 256, 0, s>>>(static_cast<const float *>(d->W), V, H, p.Ws, 0);
+        const float *w32 = static_cast<const float *>(d->W);
+        if (d->w_layout == SPO_W_HV) {
+            transpose_f32_kernel<<<dim3(grid1(H, 64), grid1(V, 64)), 256, 0, s>>>(w32, H, V, p.W32);
+            w32 = p.W32;
+        }
+        split_expand_kernel<<<grid1(V * H), 256, 0, s>>>(w32, V, H, p.Ws, 0);
         Wk = p.Ws;
-        if (d_hidden) launch_transpose(static_cast<const float *>(d->W), V, H, H, p.WT, p.V_pad, H, p.V_pad, s);
+        if (d_hidden) launch_transpose(w32, V, H, H, p.WT, p.V_pad, H, p.V_pad, s);
     } else {
         const bf16_t *Wvh = static_cast<const bf16_t *>(d->W);
         if (d->w_layout == SPO_W_HV) {

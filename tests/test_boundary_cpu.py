@@ -44,6 +44,8 @@ def test_host_side_argument_checks(L):
     one = C.c_void_p(256)  # a non-NULL, aligned dummy; never dereferenced on these paths
     # NULL pointers
     assert L.spo_tracker_update(None, None, 4, None, None, None, 1, 0.25, 0.875, 0.96, 1, None, None, None) == -2
+    assert L.spo_tracker_update_ema(None, None, 4, None, None, None, 1, 0.25, 0.875, 0.96, 1, None, None, None) == -2
+    assert L.spo_tracker_update_ema(one, one, 4, one, one, one, 1, -1.0, 0.875, 0.96, 1, None, None, None) == -1
     assert L.spo_advantages(None, None, 4, None, None, 1, 0, 0.0, 1, None, None, None, None) == -2
     assert L.spo_sample_prompts(None, None, 4, 1, 0.05, 0, 0, 0, 0, None, None, None, 0, None) == -2
     # bad scalars

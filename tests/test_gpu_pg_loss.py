@@ -37,13 +37,14 @@ def run_fwd_bwd(spo, case, w_layout=0, chunk_tokens=0, dx_dtype=torch.float32, d
     return fwd, dx, dw
 
 
-def test_tiny_spo_step_fp32(spo, oracle):
+@pytest.mark.parametrize("w_layout", [0, 1])
+def test_tiny_spo_step_fp32(spo, oracle, w_layout):
     cfg = wl.CONFIGS["C1"]
-    say("fused fp32 C1 T=512 H=128 V=1000")
+    say(f"fused fp32 C1 T=512 H=128 V=1000 w_layout={w_layout}")
     case = Case(cfg)
     assert case.T == 512
     case.set_old_from_oracle(oracle)
-    fwd, dx, dw = run_fwd_bwd(spo, case)
+    fwd, dx, dw = run_fwd_bwd(spo, case, w_layout=w_layout)
     check_forward(case, oracle, fwd, atol_logp=2e-5)
     rb = oracle.pg_loss_bwd(*case.oracle_inputs(), *case.eps)
     assert rel_l2(f64(dx), rb["d_hidden"]) < GRAD_TOL
