@@ -122,6 +122,18 @@ def test_backward_runs_over_active_tokens_only(spo, oracle, keep, chunk):
     assert not dx[torch.as_tensor(zero_rows, device="cuda")].any()
 
 
+def test_cu_seqlens_may_start_anywhere(spo, oracle):
+    # a mini-batch cut out of a packed batch keeps the batch's offsets: only differences count
+    say("fused bf16 mid, cu_seqlens shifted by a constant")
+    case = Case(MID, MID_LENGTHS, mask_frac=0.25)
+    case.set_old_from_oracle(oracle)
+    a = run_fwd_bwd(spo, case)
+    case.cu = (case.cu.astype(np.int64) + 123456).astype(np.int32)
+    b = run_fwd_bwd(spo, case)
+    assert torch.equal(a[0][0], b[0][0]) and torch.equal(a[0][1], b[0][1])
+    assert torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])
+
+
 def test_results_are_bitwise_reproducible(spo, oracle):
     say("fused bf16 mid, determinism")
     case = Case(MID, MID_LENGTHS)
