@@ -174,6 +174,7 @@ def main() -> int:
         "tflops_executed": round(4 * thv / sec / 1e12, 1),    # + the backward's recompute
         "mfma_util_executed": round(4 * thv / sec / 1e12 / PEAK_BF16_TFLOPS, 4),
         "clipped_share": round(stats[1], 5),
+        "device": torch.cuda.get_device_name(0), "torch": torch.__version__,
         "roofline": roofline,
     }
 
