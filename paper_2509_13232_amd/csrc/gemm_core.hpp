@@ -8,7 +8,7 @@
 // Data path per stage of 64 contraction elements (128 bytes = one cache line per
 // operand row; half-line rows were measured to halve the L2->LDS rate):
 //   HBM/L2 --global_load_lds_dwordx4--> LDS (two stages)  --ds_read_b128-->
-//   VGPR fragments --v_mfma_f32_32x32x16_bf16--> fp32 accumulators.
+//   VGPR fragments --v_mfma_f32_16x16x32_bf16--> fp32 accumulators.
 // Global loads go straight to LDS without passing through registers.  A tile
 // row is 8 chunks of 16 bytes; chunk c of row r is stored at chunk position
 // c ^ swz(r), which makes both the 64 lanes x 16 B fragment reads and the
@@ -16,8 +16,8 @@
 // global side (each lane fetches the chunk that belongs at its LDS slot),
 // because the DMA writes lane i at base + 16*i.
 //
-// Accumulator layout of one 32x32 block (v_mfma_f32_32x32x16_bf16): lane l
-// holds column n = l % 32 and, in register r, row m = 8*(r/4) + 4*(l/32) + r%4.
+// Accumulator layout of one 16x16 block (v_mfma_f32_16x16x32_bf16): lane l
+// holds column n = l % 16 and, in register r, row m = 4*(l/16) + r.
 // Callers put the index they reduce over or scale by per row of the tile
 // (vocabulary entries) on m and the index with per-lane constants (tokens) on n.
 #pragma once
@@ -27,7 +27,7 @@
 namespace spo {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kBK = 64;      // contraction elements per stage
 constexpr int kStages = 2;   // LDS stages
@@ -42,13 +42,18 @@ __device__ __forceinline__ int swz(int row) {
     return ((row >> 1) & 3) | (((row ^ (row >> 3)) & 1) << 2);
 }
 
-template <int BM_, int BN_, int WGM_, int WGN_>
+// MI is the edge of the MFMA block: 16 for v_mfma_f32_16x16x32_bf16, the instruction the
+// main loop is written for.  (The same tile on v_mfma_f32_32x32x16_bf16, with two
+// phase-shifted groups of wavefronts, was 4-6 % slower on the same chip.)
+template <int BM_, int BN_, int WGM_, int WGN_, int MI_ = 16>
 struct Tile {
-    static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_;
+    static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_, MI = MI_;
+    static_assert(MI == 16, "the main loop issues 16x16x32 MFMAs");
     static constexpr int NWAVE = WGM * WGN, NT = NWAVE * kWave;
     static constexpr int WM = BM / WGM, WN = BN / WGN;     // wave tile
-    static constexpr int FM = WM / 32, FN = WN / 32;       // 32x32 blocks per wave
-    static constexpr int KK = kBK / 16;                    // MFMA k-slices per stage
+    static constexpr int FM = WM / MI, FN = WN / MI;       // MI x MI blocks per wave
+    static constexpr int KK = kBK / (512 / MI);            // MFMA k-slices per stage (16 or 32 elements deep)
+    static constexpr int ACC_R = MI * MI / kWave;          // accumulator registers per block and lane
     static constexpr int A_BYTES = BM * kRowBytes, B_BYTES = BN * kRowBytes;
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int LDS_BYTES = kStages * STAGE_BYTES;
@@ -56,22 +61,36 @@ struct Tile {
     static constexpr int STAGE_LOADS = A_LOADS + B_LOADS;  // DMA instructions per thread and stage
     static_assert(BM * kChunks % NT == 0 && BN * kChunks % NT == 0, "tile rows must split evenly over the threads");
     static_assert((NT / kChunks) % 16 == 0, "swizzle must be the same for every load of a thread");
-    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile is made of 32x32 blocks");
+    static_assert(WM % MI == 0 && WN % MI == 0, "wave tile is made of MI x MI blocks");
 
-    typedef f32x16_t Acc[FM][FN];
+    typedef float AccBlock __attribute__((ext_vector_type(ACC_R)));
+    typedef AccBlock Acc[FM][FN];
 
     __device__ static __forceinline__ int wave_id() {
         return __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x) / kWave);
     }
     __device__ static __forceinline__ int wave_m0() { return (wave_id() % WGM) * WM; }
     __device__ static __forceinline__ int wave_n0() { return (wave_id() / WGM) * WN; }
-    // tile row of accumulator register r of block fm (add the block's tile origin)
+    // Accumulator layout of a 16x16 block: lane l holds column l % 16 and, in register r, row
+    // 4*(l/16) + r: a lane owns a run of four consecutive rows, a quad of lanes four consecutive
+    // columns, and the four groups of 16 lanes hold different rows of the same columns.
+    // tile row of accumulator register r of block fm
     __device__ static __forceinline__ int acc_row(int fm, int r) {
-        return wave_m0() + fm * 32 + 8 * (r >> 2) + 4 * ((threadIdx.x & 63) >> 5) + (r & 3);
+        return wave_m0() + fm * MI + 4 * ((threadIdx.x & 63) / MI) + r;
     }
     // tile column of block fn
     __device__ static __forceinline__ int acc_col(int fn) {
-        return wave_n0() + fn * 32 + (threadIdx.x & 31);
+        return wave_n0() + fn * MI + (threadIdx.x & (MI - 1));
+    }
+    static constexpr int GROUPS = kWave / MI;  // lane groups that hold different rows of the same column
+    static constexpr int RUNS = ACC_R / 4;     // runs of four consecutive rows per block and lane
+    __device__ static __forceinline__ int lane_group() { return (threadIdx.x & 63) / MI; }
+    // Row d of the wavefront's part of the tile (0 <= d < WM) lives in block fm, register r of
+    // the lanes of group g.
+    __device__ static __forceinline__ void locate(int d, int &fm, int &r, int &g) {
+        fm = d / MI;
+        g = (d >> 2) & (GROUPS - 1);
+        r = d & 3;
     }
 
     // Global -> LDS transfers of one tile: addressing and issue.
@@ -151,82 +170,85 @@ struct Tile {
     __device__ static __forceinline__ void mainloop(const char *__restrict__ A, int64_t lda_bytes, int64_t m0, int64_t M,
                                                     const char *__restrict__ B, int64_t ldb_bytes, int64_t n0, int64_t N,
                                                     int KT, char *lds, Acc &acc, bool stage0_issued = false) {
-        const int lane = threadIdx.x & 63, wave = wave_id();
+        mainloop16(A, lda_bytes, m0, M, B, ldb_bytes, n0, N, KT, lds, acc, stage0_issued);
+    }
+
+    // A lone wavefront cannot issue these four-pass MFMAs back to back, so
+    // the two wavefronts of a SIMD multiply at the same time and each hides its own fragment
+    // reads between its MFMAs (one read per two MFMAs, into a second register set for the next
+    // k-slice of 32).  One barrier per step, between the two k-slices: before it a wavefront has
+    // all its reads of stage s in registers and its share of stage s+1 landed; after it stage s+1
+    // may be read and the buffer of stage s is refilled with stage s+2 (one DMA instruction per
+    // four MFMAs).
+    __device__ static __forceinline__ void mainloop16(const char *__restrict__ A, int64_t lda_bytes, int64_t m0, int64_t M,
+                                                      const char *__restrict__ B, int64_t ldb_bytes, int64_t n0, int64_t N,
+                                                      int KT, char *lds, Acc &acc, bool stage0_issued) {
+        static_assert(KK == 2 && kStages == 2, "two k-slices per stage, two stages");
+        static_assert((FM + FN) * 2 <= FM * FN && STAGE_LOADS * 4 <= FM * FN, "reads and DMA fit between the MFMAs of a slice");
+        const int lane = threadIdx.x & 63;
         const Dma d(A, lda_bytes, m0, M, B, ldb_bytes, n0, N, lds);
-        auto wait_dma = [] { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
-        // ---- fragment addressing: lane reads row (l%32) of a 32-row block, chunk 2*kk + l/32
+        // lane reads row (l%16) of a 16-row block, chunk 4*kk + l/16
         const int fr_sw = swz(lane & 15);
         int fr_off[KK];
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk) fr_off[kk] = (lane & 31) * kRowBytes + (((2 * kk + (lane >> 5)) ^ fr_sw) * 16);
+        for (int kk = 0; kk < KK; ++kk) fr_off[kk] = (lane & 15) * kRowBytes + (((4 * kk + (lane >> 4)) ^ fr_sw) * 16);
         const int a_base = wave_m0() * kRowBytes, b_base = A_BYTES + wave_n0() * kRowBytes;
-
-        // Two groups of four wavefronts (one of each per SIMD) run half a step apart:
-        // while one group multiplies, the other reads its fragments from LDS, so the
-        // MFMA pipe of every SIMD always has a wavefront to serve.  Barrier j of one
-        // group meets barrier j of the other; group 1 passes one extra barrier first
-        // and group 0 one extra at the end.  With I(j) the interval after barrier j,
-        // group 0 reads stage s in I(2s) and multiplies in I(2s+1); group 1 reads in
-        // I(2s+1) and multiplies in I(2s+2).  The buffer of stage s+1 is free from
-        // barrier 2s on and must be complete at barrier 2s+2, so its DMA is issued in
-        // I(2s) and awaited at the end of I(2s+1).  The address unit takes about 16
-        // cycles per DMA instruction and a burst of them blocks the issuing
-        // wavefront: group 1, which multiplies during I(2s), feeds its share one
-        // instruction per two MFMAs, and group 0 issues its share behind its
-        // fragment reads.
-        static_assert(NWAVE == 8, "the main loop is written for two groups of four wavefronts");
-        static_assert(kStages == 2, "the schedule below is for two stages");
-        const int group = wave >> 2;
         auto fence_barrier = [] {
             __builtin_amdgcn_sched_barrier(0);
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
         };
+        bf16x8_t af[2][FM], bf[2][FN];
+        // fragment r (0..FM+FN-1) of k-slice kk of stage kt into register set buf
+        auto read_frag = [&](int kt, int kk, int buf, int r) {
+            const char *st = lds + (kt % kStages) * STAGE_BYTES;
+            if (r < FM) af[buf][r] = *reinterpret_cast<const bf16x8_t *>(st + a_base + r * (16 * kRowBytes) + fr_off[kk]);
+            else bf[buf][r - FM] = *reinterpret_cast<const bf16x8_t *>(st + b_base + (r - FM) * (16 * kRowBytes) + fr_off[kk]);
+        };
         if (!stage0_issued) {
             __syncthreads();  // every wave is done with the previous contents of lds
             d.stage(0);
         }
-        wait_dma();
-        fence_barrier();
-        if (group == 1) {
-            if (KT > 1) d.stage(1);
-            fence_barrier();
+        if (KT > 1) {
+            d.stage(1);
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(STAGE_LOADS) : "memory");  // loads return in order: stage 0 has landed
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
+        fence_barrier();
+#pragma unroll
+        for (int r = 0; r < FM + FN; ++r) read_frag(0, 0, 0, r);
         for (int kt = 0; kt < KT; ++kt) {
-            const char *st = lds + (kt % kStages) * STAGE_BYTES;
-            bf16x8_t af[FM][KK], bf[FN][KK];
+            // ---- slice 0 of stage kt, reading its slice 1 between the MFMAs
 #pragma unroll
-            for (int kk = 0; kk < KK; ++kk) {
-#pragma unroll
-                for (int fm = 0; fm < FM; ++fm)
-                    af[fm][kk] = *reinterpret_cast<const bf16x8_t *>(st + a_base + fm * (32 * kRowBytes) + fr_off[kk]);
-#pragma unroll
-                for (int fn = 0; fn < FN; ++fn)
-                    bf[fn][kk] = *reinterpret_cast<const bf16x8_t *>(st + b_base + fn * (32 * kRowBytes) + fr_off[kk]);
-            }
-            if (group == 0) {
-                if (kt + 1 < KT) d.stage(kt + 1);
-            } else {
-                wait_dma();  // my share of stage kt+1, issued during the previous multiply phase
-            }
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // fragments are in registers
-            fence_barrier();
-            __builtin_amdgcn_s_setprio(1);
-            const bool feed = group == 1 && kt + 2 < KT;  // wave-uniform
-#pragma unroll
-            for (int j = 0; j < KK * FM * FN; ++j) {
-                const int kk = j / (FM * FN), fm = (j / FN) % FM, fn = j % FN;
-                if (j % 2 == 0 && j / 2 < STAGE_LOADS) {
-                    if (feed) d.one(kt + 2, j / 2);
+            for (int j = 0; j < FM * FN; ++j) {
+                const int fm = j / FN, fn = j % FN;
+                if (j % 2 == 0 && j / 2 < FM + FN) {
+                    read_frag(kt, 1, 1, j / 2);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[fm][kk], bf[fn][kk], acc[fm][fn], 0, 0, 0);
+                acc[fm][fn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[0][fm], bf[0][fn], acc[fm][fn], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            __builtin_amdgcn_s_setprio(0);
-            if (group == 0) wait_dma();  // my share of stage kt+1
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
             fence_barrier();
+            const bool more = kt + 1 < KT, feed = kt + 2 < KT;
+            // ---- slice 1, reading slice 0 of stage kt+1 and feeding the DMA of stage kt+2
+#pragma unroll
+            for (int j = 0; j < FM * FN; ++j) {
+                const int fm = j / FN, fn = j % FN;
+                if (j % 2 == 0 && j / 2 < FM + FN) {
+                    if (more) read_frag(kt + 1, 0, 0, j / 2);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if (j % 4 == 1 && j / 4 < STAGE_LOADS) {
+                    if (feed) d.one(kt + 2, j / 4);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                acc[fm][fn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[1][fm], bf[1][fn], acc[fm][fn], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
-        if (group == 0) fence_barrier();
     }
 
     __device__ static __forceinline__ void zero(Acc &acc) {
@@ -235,7 +257,7 @@ struct Tile {
 #pragma unroll
             for (int fn = 0; fn < FN; ++fn)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[fm][fn][r] = 0.0f;
+                for (int r = 0; r < ACC_R; ++r) acc[fm][fn][r] = 0.0f;
     }
 };
 
