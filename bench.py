@@ -29,7 +29,7 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 # scaled by what the same counter reads for a plain 1 GiB copy (profiles/step_c3_hbm_traffic.md).
 # Valid only for the kernels as profiled: None for any other workload or chunk size.
 TRAFFIC_BYTES_PER_LAUNCH = {
-    ("C3", 0): {"fwd_sweep": 784.3e9, "bwd_recompute": 88.1e9, "bwd_dhidden": 68.2e9, "bwd_dw": 65.5e9},
+    ("C3", 0): {"fwd_sweep": 764.4e9, "bwd_recompute": 84.8e9, "bwd_dhidden": 60.7e9, "bwd_dw": 74.7e9},
 }
 
 
