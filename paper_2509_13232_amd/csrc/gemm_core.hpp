@@ -1,9 +1,11 @@
 // bf16 MFMA contraction core for gfx950 (CDNA4, 64-wide wavefronts).
 //
 // Computes a BM x BN tile of  D[m][n] = sum_k A[m][k] * B[n][k]  where both
-// operands are row-major with the contraction index contiguous.  All three
-// contractions of the loss (logits = W h, dHidden = dZ W, dW = dZ^T X) are
-// brought to this form by the callers, so there is one main loop to tune.
+// operands are row-major with the contraction index contiguous (mainloop: logits =
+// W h and dHidden = dZ W), or of  D[m][n] = sum_k A[k][m] * B[k][n]  where the
+// contraction index is the row index of both (mainloop_kmajor: dW = dZ^T X, which
+// contracts over tokens, read from the same token-major dZ and hidden rows).  The two
+// loops share the tile shape, the schedule and the accumulator layout.
 //
 // Data path per stage of 64 contraction elements (128 bytes = one cache line per
 // operand row; half-line rows were measured to halve the L2->LDS rate):
@@ -246,6 +248,169 @@ struct Tile {
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 acc[fm][fn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[1][fm], bf[1][fn], acc[fm][fn], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+
+    // ---- operands with the contraction index as the ROW index: A[k][m], B[k][n] ----
+    // LDS stage of an operand: kBK rows of BM (BN) elements = 512 bytes = 32 chunks of 16 bytes,
+    // chunk c of row r at position c ^ ksw(r).  ksw moves bits 1-2 of the position with the row
+    // inside a group of four and bits 3-4 with the group of eight rows, so the 8-byte pieces a
+    // transposing read collects (4 rows x 32 bytes per group of 16 lanes, the four groups 8 rows
+    // apart) fall on distinct banks, and so do the linear DMA writes.
+    __device__ static __forceinline__ int ksw(int r) { return ((r & 3) << 1) | (((r >> 3) & 3) << 3); }
+    static constexpr int K_ROWB = BM * 2;                  // bytes per row of a stage
+    static constexpr int K_CH = K_ROWB / 16;               // chunks per row
+    static constexpr int K_LOADS = kBK * K_CH / NT;        // DMA instructions per thread, operand and stage
+    static_assert(BM == BN && K_CH == 32 && kBK * K_CH % NT == 0 && 2 * K_LOADS == STAGE_LOADS,
+                  "row-index-contracted stages have the size and DMA count of the others");
+
+    // Global -> LDS transfers for mainloop_kmajor.  Slot q = i*NT + tid of an operand's stage
+    // <-> (row q / K_CH, position q % K_CH): one instruction moves two whole rows of 512 bytes.
+    struct DmaK {
+        const char *a_col, *b_col;  // &A[0][m0], &B[0][n0] (wave-uniform)
+        int64_t lda, ldb;           // row strides in bytes
+        uint32_t oa[K_LOADS], ob[K_LOADS];
+        uint32_t lds_wave;
+        // Mr, Nr: readable length of a row of A, B (multiples of 8 elements); chunks past it are
+        // fetched from the row's last readable chunk (the caller masks those columns)
+        __device__ __forceinline__ DmaK(const char *A, int64_t lda_bytes, int64_t m0, int64_t Mr, const char *B,
+                                        int64_t ldb_bytes, int64_t n0, int64_t Nr, char *lds) {
+            const int tid = threadIdx.x;
+            auto uniform = [](const char *p) {
+                const uint64_t u = reinterpret_cast<uint64_t>(p);
+                const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(u));
+                const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(u >> 32));
+                return reinterpret_cast<const char *>((static_cast<uint64_t>(hi) << 32) | lo);
+            };
+            a_col = uniform(A + m0 * 2);
+            b_col = uniform(B + n0 * 2);
+            lda = lda_bytes;
+            ldb = ldb_bytes;
+            const int a_last = (Mr - m0 >= BM ? K_CH : static_cast<int>(Mr - m0) / 8) - 1;
+            const int b_last = (Nr - n0 >= BN ? K_CH : static_cast<int>(Nr - n0) / 8) - 1;
+#pragma unroll
+            for (int i = 0; i < K_LOADS; ++i) {
+                const int q = i * NT + tid, row = q / K_CH, c = (q % K_CH) ^ ksw(row);
+                oa[i] = static_cast<uint32_t>(row * lda_bytes + (c < a_last ? c : a_last) * 16);
+                ob[i] = static_cast<uint32_t>(row * ldb_bytes + (c < b_last ? c : b_last) * 16);
+            }
+            lds_wave = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char *)lds)) +
+                       wave_id() * (kWave * 16);
+        }
+        __device__ __forceinline__ void one(int kt, int i) const {
+            const uint32_t la = lds_wave + (kt % kStages) * STAGE_BYTES;
+            if (i < K_LOADS) Dma::dma(a_col + static_cast<int64_t>(kt) * kBK * lda, oa[i], la + i * (NT * 16));
+            else Dma::dma(b_col + static_cast<int64_t>(kt) * kBK * ldb, ob[i - K_LOADS], la + A_BYTES + (i - K_LOADS) * (NT * 16));
+        }
+        __device__ __forceinline__ void stage(int kt) const {
+#pragma unroll
+            for (int i = 0; i < STAGE_LOADS; ++i) one(kt, i);
+        }
+    };
+
+    // acc += sum_k A[k][m0..] * B[k][n0..] over k < kBK*KT; every row k < kBK*KT of both operands
+    // must be readable.  Same schedule as mainloop16; the fragments come out of LDS with
+    // ds_read_b64_tr_b16: within a group of 16 lanes, lane i receives element i%4 of the four
+    // source lanes i/4, i/4+4, i/4+8, i/4+12.  Source lane s points at row k0 + s/4, columns
+    // 4*(s%4).. of a 16-column block, so lane i ends up with rows k0..k0+3 of column i; the
+    // group index selects k0 = 8*(l/16) and a second read 4 rows down completes the 8 values
+    // per lane that the MFMA wants (two reads per fragment, one read per MFMA while they last).
+    __device__ static __forceinline__ void mainloop_kmajor(const char *__restrict__ A, int64_t lda_bytes, int64_t m0, int64_t Mr,
+                                                           const char *__restrict__ B, int64_t ldb_bytes, int64_t n0, int64_t Nr,
+                                                           int KT, char *lds, Acc &acc) {
+        typedef short v4s __attribute__((ext_vector_type(4)));
+        typedef short v8s __attribute__((ext_vector_type(8)));
+        static_assert(KK == 2 && kStages == 2, "two k-slices per stage, two stages");
+        constexpr int NR = 2 * (FM + FN);  // reads per k-slice
+        static_assert(NR <= FM * FN && STAGE_LOADS * 4 <= FM * FN, "reads and DMA fit between the MFMAs of a slice");
+        static_assert((32 + 4) * K_ROWB < 65536, "slice and half offsets fit the read's offset field");
+        const int lane = threadIdx.x & 63;
+        const DmaK d(A, lda_bytes, m0, Mr, B, ldb_bytes, n0, Nr, lds);
+        const int G = lane >> 4, sl = lane & 15;
+        // LDS address of this lane's source piece of a block, slice 0, first half, stage 0.  The
+        // slice adds 32 rows and the half 4 rows (neither changes ksw); the stage is toggled in.
+        auto src_off = [&](int col0) {
+            const int row = 8 * G + (sl >> 2);
+            const int col = col0 + 4 * (sl & 3);
+            return row * K_ROWB + (((col >> 3) ^ ksw(row)) << 4) + ((col >> 2) & 1) * 8;
+        };
+        const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char *)lds));
+        uint32_t a_addr[FM], b_addr[FN];
+#pragma unroll
+        for (int b = 0; b < FM; ++b) a_addr[b] = lds0 + src_off(wave_m0() + b * MI);
+#pragma unroll
+        for (int b = 0; b < FN; ++b) b_addr[b] = lds0 + A_BYTES + src_off(wave_n0() + b * MI);
+        int to_other = STAGE_BYTES;  // distance to the stage the addresses do not point at
+        auto other_stage = [&] {
+#pragma unroll
+            for (int b = 0; b < FM; ++b) a_addr[b] += to_other;
+#pragma unroll
+            for (int b = 0; b < FN; ++b) b_addr[b] += to_other;
+            to_other = -to_other;
+        };
+        auto fence_barrier = [] {
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        v4s ah[2][FM][2], bh[2][FN][2];  // [register set][block][half of the 8 contraction values]
+        // read r (0 .. NR-1) of k-slice kk of the stage the addresses point at, into register set buf
+        auto read_half = [&](int kk, int buf, int r) {
+            const int blk = r >> 1, h = r & 1;
+            const int off = (32 * kk + 4 * h) * K_ROWB;
+            if (blk < FM)
+                ah[buf][blk][h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (v4s __attribute__((address_space(3))) *)(uintptr_t)(a_addr[blk] + off));
+            else
+                bh[buf][blk - FM][h] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (v4s __attribute__((address_space(3))) *)(uintptr_t)(b_addr[blk - FM] + off));
+        };
+        auto frag = [](const v4s (&p)[2]) {
+            const v8s v = __builtin_shufflevector(p[0], p[1], 0, 1, 2, 3, 4, 5, 6, 7);
+            return __builtin_bit_cast(bf16x8_t, v);
+        };
+        __syncthreads();  // every wave is done with the previous contents of lds
+        d.stage(0);
+        if (KT > 1) {
+            d.stage(1);
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(STAGE_LOADS) : "memory");  // loads return in order: stage 0 has landed
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+        fence_barrier();
+#pragma unroll
+        for (int r = 0; r < NR; ++r) read_half(0, 0, r);
+        for (int kt = 0; kt < KT; ++kt) {
+            // ---- slice 0 of stage kt, reading its slice 1 between the MFMAs
+#pragma unroll
+            for (int j = 0; j < FM * FN; ++j) {
+                const int fm = j / FN, fn = j % FN;
+                if (j < NR) {
+                    read_half(1, 1, j);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                acc[fm][fn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(frag(ah[0][fm]), frag(bh[0][fn]), acc[fm][fn], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            fence_barrier();
+            other_stage();
+            const bool more = kt + 1 < KT, feed = kt + 2 < KT;
+            // ---- slice 1, reading slice 0 of stage kt+1 and feeding the DMA of stage kt+2
+#pragma unroll
+            for (int j = 0; j < FM * FN; ++j) {
+                const int fm = j / FN, fn = j % FN;
+                if (j < NR) {
+                    if (more) read_half(0, 0, j);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if (j % 4 == 1 && j / 4 < STAGE_LOADS) {
+                    if (feed) d.one(kt + 2, j / 4);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                acc[fm][fn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(frag(ah[1][fm]), frag(bh[1][fn]), acc[fm][fn], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }

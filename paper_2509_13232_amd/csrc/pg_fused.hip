@@ -300,19 +300,18 @@ fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const
 // ----------------------------------------------------------------------------
 // backward, step 1: recompute a logits tile and emit its bf16 gradient
 // ----------------------------------------------------------------------------
-// dz[t][v] = g[t] * ([v == target[t]] - exp(z[t][v] - lse[t])), written both as
-// dZ[t][v] (row stride ldz, vocabulary contiguous: operand of dHidden) and as
-// dZT[v][t] (row stride ldzt, tokens contiguous: operand of dW).  Columns
-// V <= v < V_pad of dZ and tokens past T_valid are written as zeros.  Token tiles
-// that start at or after the number of active rows of this chunk (device value
-// n_act[0] - row_base) are skipped altogether.
+// dz[t][v] = g[t] * ([v == target[t]] - exp(z[t][v] - lse[t])), written as
+// dZ[t][v] (row stride ldz, vocabulary contiguous): dHidden contracts it over v
+// and dW over t, both from this one copy.  Columns V <= v < V_pad of dZ and tokens
+// past T_valid are written as zeros.  Token tiles that start at or after the
+// number of active rows of this chunk (device value n_act[0] - row_base) are
+// skipped altogether.
 __global__ void __launch_bounds__(TL::NT)
 recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, int64_t V_pad,
                     const char *__restrict__ X, int64_t ldx_bytes, int64_t T_valid, int KT,
                     const int32_t *__restrict__ target, const float *__restrict__ lse,
                     const float *__restrict__ g, int64_t nVt, int64_t nTt, bf16_t *__restrict__ dZ,
-                    int64_t ldz, bf16_t *__restrict__ dZT, int64_t ldzt, const int32_t *__restrict__ n_act,
-                    int64_t row_base) {
+                    int64_t ldz, const int32_t *__restrict__ n_act, int64_t row_base) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     int64_t tm, tn;
     if (!TileOrder(nVt, nTt).tile(blockIdx.x, tm, tn)) return;
@@ -330,17 +329,13 @@ recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, in
 #pragma unroll
                     for (int fn = 0; fn < TL::FN; ++fn) acc[fm][fn][r] = kNegBig;
     }
-    // Both copies go out through LDS (the operand stages are free now).  A lane holds runs of
+    // The tile goes out through LDS (the operand stages are free now).  A lane holds runs of
     // four consecutive vocabulary entries of ONE token, so stored directly a wavefront would
     // scatter 64 pieces of 8 bytes over many rows per instruction; from LDS every store
     // instruction writes two full rows of 512 bytes.
-    //   first copy:  256 token rows x 512 B, 16-byte chunk c of row t at position c ^ (t % 32)
-    //   second copy: 256 vocabulary rows x 512 B, chunk c of row v at position c ^ ((v % 8) << 2)
-    static_assert(TL::LDS_BYTES >= TL::BN * 512 && TL::BM * 2 == 512 && TL::BN * 2 == 512,
-                  "a tile of bf16 gradients fits the operand stages");
+    //   256 token rows x 512 B, 16-byte chunk c of row t at position c ^ (t % 32)
+    static_assert(TL::LDS_BYTES >= TL::BN * 512 && TL::BM * 2 == 512, "a tile of bf16 gradients fits the operand stages");
     const int lane = threadIdx.x & 63;
-    const int quad_lane = threadIdx.x & 3;
-    uint2 pk[TL::FN][TL::FM][TL::RUNS];  // bf16 gradients: .x = rows +0,+1, .y = rows +2,+3 of a run, my token
 #pragma unroll
     for (int fn = 0; fn < TL::FN; ++fn) {
         const int tl = TL::acc_col(fn);
@@ -370,71 +365,31 @@ recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, in
                     for (int i = 0; i < 4; ++i)
                         if ((rq & 3) == i) dz[i] += gt;
                 }
-                pk[fn][fm][r4].x = pack_bf16x2_rn(dz[0], dz[1]);
-                pk[fn][fm][r4].y = pack_bf16x2_rn(dz[2], dz[3]);
-                if (dZ)
-                    *reinterpret_cast<uint2 *>(lds + tl * 512 + (((vl >> 3) ^ (tl & 31)) << 4) + (vl & 4) * 2) = pk[fn][fm][r4];
+                uint2 pk;  // bf16 gradients: .x = rows +0,+1, .y = rows +2,+3 of the run, my token
+                pk.x = pack_bf16x2_rn(dz[0], dz[1]);
+                pk.y = pack_bf16x2_rn(dz[2], dz[3]);
+                *reinterpret_cast<uint2 *>(lds + tl * 512 + (((vl >> 3) ^ (tl & 31)) << 4) + (vl & 4) * 2) = pk;
             }
         }
     }
+    __syncthreads();
+    // every wavefront writes 32 token rows, two rows (2 x 512 contiguous bytes) per store
     const int ci = lane & 31;  // 16-byte chunk of a row that this lane writes out
-    if (dZ) {
-        __syncthreads();
-        // every wavefront writes 32 token rows, two rows (2 x 512 contiguous bytes) per store
-        const bool col_ok = m0 + ci * 8 < V_pad;
+    const bool col_ok = m0 + ci * 8 < V_pad;
 #pragma unroll
-        for (int i = 0; i < TL::BN / TL::NWAVE / 2; ++i) {
-            const int tl = TL::wave_id() * (TL::BN / TL::NWAVE) + 2 * i + (lane >> 5);
-            const uint4 v = *reinterpret_cast<const uint4 *>(lds + tl * 512 + ((ci ^ (tl & 31)) << 4));
-            if (col_ok) *reinterpret_cast<uint4 *>(dZ + (n0 + tl) * ldz + m0 + ci * 8) = v;
-        }
-    }
-    if (dZT) {
-        if (dZ) __syncthreads();  // the first copy has been read
-#pragma unroll
-        for (int fn = 0; fn < TL::FN; ++fn)
-#pragma unroll
-            for (int fm = 0; fm < TL::FM; ++fm)
-#pragma unroll
-                for (int r4 = 0; r4 < TL::RUNS; ++r4) {
-                    // The four lanes of a quad hold four consecutive tokens of the same four
-                    // vocabulary rows: transpose that 4x4 block in registers so that lane j
-                    // of the quad holds row +j for the quad's four tokens (8 bytes).
-                    const int j = quad_lane;
-                    const uint32_t x = pk[fn][fm][r4].x, y = pk[fn][fm][r4].y;
-                    // step 1: 2x2 blocks of 16-bit values between lanes j and j^1
-                    const uint32_t xn = __builtin_amdgcn_mov_dpp(x, 0xB1, 0xF, 0xF, true);  // quad_perm [1,0,3,2]
-                    const uint32_t yn = __builtin_amdgcn_mov_dpp(y, 0xB1, 0xF, 0xF, true);
-                    // even lane: (own low, neighbour low); odd lane: (neighbour high, own high)
-                    // (v_perm_b32: selector bytes 0-3 pick from the second operand, 4-7 from the first)
-                    const uint32_t sel = (j & 1) ? 0x03020706u : 0x05040100u;
-                    const uint32_t x1 = __builtin_amdgcn_perm(xn, x, sel);
-                    const uint32_t y1 = __builtin_amdgcn_perm(yn, y, sel);
-                    // now x1 = row (j&1) of tokens pair (j>>1), y1 = row 2+(j&1) of the same pair
-                    // step 2: 32-bit exchange between lanes j and j^2
-                    const uint32_t give = (j & 2) ? x1 : y1;
-                    const uint32_t got = __builtin_amdgcn_mov_dpp(give, 0x4E, 0xF, 0xF, true);  // quad_perm [2,3,0,1]
-                    uint2 row;
-                    row.x = (j & 2) ? got : x1;
-                    row.y = (j & 2) ? y1 : got;
-                    const int vr = TL::acc_row(fm, r4 * 4) + j;  // tile-local vocabulary row
-                    const int tq = TL::acc_col(fn) - j;           // first of the quad's 4 tokens
-                    *reinterpret_cast<uint2 *>(lds + vr * 512 + (((tq >> 3) ^ ((vr & 7) << 2)) << 4) + (tq & 4) * 2) = row;
-                }
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < TL::BM / TL::NWAVE / 2; ++i) {
-            const int vr = TL::wave_id() * (TL::BM / TL::NWAVE) + 2 * i + (lane >> 5);
-            const uint4 v = *reinterpret_cast<const uint4 *>(lds + vr * 512 + ((ci ^ ((vr & 7) << 2)) << 4));
-            if (m0 + vr < V) *reinterpret_cast<uint4 *>(dZT + (m0 + vr) * ldzt + n0 + ci * 8) = v;
-        }
+    for (int i = 0; i < TL::BN / TL::NWAVE / 2; ++i) {
+        const int tl = TL::wave_id() * (TL::BN / TL::NWAVE) + 2 * i + (lane >> 5);
+        const uint4 v = *reinterpret_cast<const uint4 *>(lds + tl * 512 + ((ci ^ (tl & 31)) << 4));
+        if (col_ok) *reinterpret_cast<uint4 *>(dZ + (n0 + tl) * ldz + m0 + ci * 8) = v;
     }
 }
 
 // ----------------------------------------------------------------------------
 // backward, steps 2 and 3: plain contraction with a store / accumulate epilogue
 // ----------------------------------------------------------------------------
-// out[row(m)*ldo + n] (=|+=) sum_k A[m][k] B[n][k]
+// out[row(m)*ldo + n] (=|+=) sum_k A[m][k] B[n][k], or with KMajor
+// sum_k A[k][m] B[k][n] (rows of A and B are then readable up to the next multiple
+// of 8 elements past M and N).
 // With n_act != NULL the extent that holds active tokens is read on the device
 // (rows = active_rows(n_act, row_base, .)): limit == kLimitRows keeps only the first
 // `rows` rows of A and stores row m at out row row_map[m] (dHidden: scatter back to the
@@ -442,6 +397,7 @@ recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, in
 // the contraction index, rounded up to whole tiles of tokens (dW).
 constexpr int kLimitRows = 1, kLimitK = 2;
 
+template <bool KMajor>
 __global__ void __launch_bounds__(TL::NT)
 gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, const char *__restrict__ B,
                   int64_t ldb_bytes, int64_t N, int KT, void *__restrict__ out, int64_t ldo, int out_dtype,
@@ -463,7 +419,10 @@ gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, cons
     }
     TL::Acc acc;
     TL::zero(acc);
-    if (KT > 0) TL::mainloop(A, lda_bytes, m0, M, B, ldb_bytes, n0, N, KT, lds, acc);
+    if (KT > 0) {
+        if (KMajor) TL::mainloop_kmajor(A, lda_bytes, m0, (M + 7) & ~int64_t(7), B, ldb_bytes, n0, (N + 7) & ~int64_t(7), KT, lds, acc);
+        else TL::mainloop(A, lda_bytes, m0, M, B, ldb_bytes, n0, N, KT, lds, acc);
+    }
 #pragma unroll
     for (int fn = 0; fn < TL::FN; ++fn) {
         const int64_t n = n0 + TL::acc_col(fn);
@@ -497,7 +456,9 @@ static int set_lds_limit() {
                                     hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
     e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(recompute_dz_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
-    e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_store_kernel),
+    e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_store_kernel<false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
+    e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_store_kernel<true>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
     return e == hipSuccess ? SPO_OK : SPO_EHIP;
 }
@@ -597,10 +558,10 @@ int fused_fwd(const spo_pg_desc *d, float *loss, float *logp, float *lse, float 
 }
 
 struct BwdPlan {
-    int64_t Tc, ldt, V_pad, Kc, T_pad;  // ldt: row stride of the token-contiguous scratch (dZT, XT)
+    int64_t Tc, V_pad, Kc, T_pad;
     double *count;
     float *g, *dW_acc;
-    bf16_t *WT, *XT, *dZ, *dZT, *Xs, *Ws, *Wvh;
+    bf16_t *WT, *Xb, *dZ, *Xs, *Ws, *Wvh;  // Xb: bf16 copy of the gathered rows of an fp32 hidden
     float *W32;  // [V,H] copy of an fp32 head given as [H,V]
     int32_t *act_idx, *n_act, *tgt_c;  // active-token list, its length, per-chunk compact copies
     float *lse_c, *g_c;
@@ -613,7 +574,6 @@ static BwdPlan plan_bwd(const spo_pg_desc *d, int64_t chunk_tokens, void *ws, bo
     const int64_t Tmax = round_up(std::max<int64_t>(d->T, 1), TL::BN);
     int64_t tc = chunk_tokens > 0 ? chunk_tokens : kDefaultChunk;
     p.Tc = std::min(round_up(tc, TL::BN), Tmax);
-    p.ldt = p.Tc + 64;  // keeps the rows of a tile off a common power-of-two stride
     p.T_pad = Tmax;
     p.V_pad = round_up(d->V, kBK);
     p.Kc = d->dtype == SPO_FP32 ? kSplitTerms * d->H : d->H;
@@ -627,13 +587,12 @@ static BwdPlan plan_bwd(const spo_pg_desc *d, int64_t chunk_tokens, void *ws, bo
     p.g_c = a.take<float>(p.Tc);
     p.Xc = a.take<char>(static_cast<size_t>(p.Tc) * d->H * (d->dtype == SPO_FP32 ? 4 : 2));
     p.WT = a.take<bf16_t>(static_cast<size_t>(d->H) * p.V_pad);
-    p.XT = a.take<bf16_t>(static_cast<size_t>(d->H) * p.ldt);
     p.dZ = a.take<bf16_t>(static_cast<size_t>(p.Tc) * p.V_pad);
-    p.dZT = a.take<bf16_t>(static_cast<size_t>(d->V) * p.ldt);
-    p.Xs = p.Ws = p.Wvh = nullptr;
+    p.Xb = p.Xs = p.Ws = p.Wvh = nullptr;
     p.dW_acc = nullptr;
     p.W32 = nullptr;
     if (d->dtype == SPO_FP32) {
+        p.Xb = a.take<bf16_t>(static_cast<size_t>(p.Tc) * d->H);
         p.Xs = a.take<bf16_t>(static_cast<size_t>(p.Tc) * p.Kc);
         p.Ws = a.take<bf16_t>(static_cast<size_t>(d->V) * p.Kc);
         if (d->w_layout == SPO_W_HV) p.W32 = a.take<float>(static_cast<size_t>(d->V) * d->H);
@@ -658,11 +617,12 @@ static void launch_transpose(const SrcT *src, int64_t R, int64_t C, int64_t ld_s
                                                                                          R_pad, C_pad, ld_dst);
 }
 
+template <bool KMajor>
 static void launch_gemm(const bf16_t *A, int64_t lda, int64_t M, const bf16_t *B, int64_t ldb, int64_t N, int64_t K,
                         void *out, int64_t ldo, int out_dtype, int accumulate, const int32_t *n_act, int64_t row_base,
                         int limit, const int32_t *row_map, hipStream_t s) {
     const TileOrder ord(ceil_div(M, TL::BM), ceil_div(N, TL::BN));
-    gemm_store_kernel<<<static_cast<unsigned>(ord.blocks()), TL::NT, TL::LDS_BYTES, s>>>(
+    gemm_store_kernel<KMajor><<<static_cast<unsigned>(ord.blocks()), TL::NT, TL::LDS_BYTES, s>>>(
         reinterpret_cast<const char *>(A), lda * 2, M, reinterpret_cast<const char *>(B), ldb * 2, N,
         static_cast<int>(K / kBK), out, ldo, out_dtype, accumulate, n_act, row_base, limit, row_map);
 }
@@ -721,7 +681,7 @@ int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float g
         // rows [t0, t0 + Tcp) of the compact order; how many of them exist is known on the
         // device only, so every launch is sized for the most there can be and trims itself
         const int64_t Tcp = round_up(std::min(p.Tc, T - t0), TL::BN);
-        const bf16_t *Xk;
+        const bf16_t *Xk, *Xrows;  // operand of the recompute; the rows as plain bf16 (operand of dW)
         if (d->dtype == SPO_FP32) {
             float *xc = static_cast<float *>(p.Xc);
             gather_chunk_kernel<float><<<static_cast<unsigned>(Tcp), 256, 0, s>>>(
@@ -729,14 +689,14 @@ int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float g
                 p.tgt_c, p.lse_c, p.g_c);
             split_expand_kernel<<<grid1(Tcp * H), 256, 0, s>>>(xc, Tcp, H, p.Xs, 1);
             Xk = p.Xs;
-            if (d_W) launch_transpose(xc, Tcp, H, H, p.XT, Tcp, H, p.ldt, s);
+            if (d_W) f32_to_bf16_kernel<<<grid1(Tcp * H), 256, 0, s>>>(xc, p.Xb, Tcp * H);
+            Xrows = p.Xb;
         } else {
             bf16_t *xc = static_cast<bf16_t *>(p.Xc);
             gather_chunk_kernel<bf16_t><<<static_cast<unsigned>(Tcp), 256, 0, s>>>(
                 static_cast<const bf16_t *>(d->hidden), H, p.act_idx, p.n_act, t0, Tcp, d->target, lse, p.g, xc,
                 p.tgt_c, p.lse_c, p.g_c);
-            Xk = xc;
-            if (d_W) launch_transpose(xc, Tcp, H, H, p.XT, Tcp, H, p.ldt, s);
+            Xk = Xrows = xc;
         }
         {
             const TileOrder ord(nVt, Tcp / TL::BN);
@@ -744,20 +704,21 @@ int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float g
             recompute_dz_kernel<<<static_cast<unsigned>(ord.blocks()), TL::NT, TL::LDS_BYTES, s>>>(
                 reinterpret_cast<const char *>(Wk), p.Kc * 2, V, p.V_pad, reinterpret_cast<const char *>(Xk), p.Kc * 2,
                 Tcp, static_cast<int>(p.Kc / kBK), p.tgt_c, p.lse_c, p.g_c, nVt, Tcp / TL::BN,
-                d_hidden ? p.dZ : nullptr, p.V_pad, d_W ? p.dZT : nullptr, p.ldt, p.n_act, t0);
+                p.dZ, p.V_pad, p.n_act, t0);
         }
         if (d_hidden) {
             ScopedKernelTimer timer(kTimeDHidden, s);
-            launch_gemm(p.dZ, p.V_pad, Tcp, p.WT, p.V_pad, H, p.V_pad, d_hidden, H, d_hidden_dtype, 0, p.n_act, t0,
+            launch_gemm<false>(p.dZ, p.V_pad, Tcp, p.WT, p.V_pad, H, p.V_pad, d_hidden, H, d_hidden_dtype, 0, p.n_act, t0,
                         kLimitRows, p.act_idx + t0, s);
         }
         if (d_W) {
             const int acc = (c > 0 || accumulate_dW) ? 1 : 0;
             ScopedKernelTimer timer(kTimeDW, s);
+            // contraction over the chunk's tokens, the row index of both dZ and the gathered hidden rows
             if (d->w_layout == SPO_W_VH)
-                launch_gemm(p.dZT, p.ldt, V, p.XT, p.ldt, H, Tcp, dW32, H, SPO_FP32, acc, p.n_act, t0, kLimitK, nullptr, s);
+                launch_gemm<true>(p.dZ, p.V_pad, V, Xrows, H, H, Tcp, dW32, H, SPO_FP32, acc, p.n_act, t0, kLimitK, nullptr, s);
             else
-                launch_gemm(p.XT, p.ldt, H, p.dZT, p.ldt, V, Tcp, dW32, V, SPO_FP32, acc, p.n_act, t0, kLimitK, nullptr, s);
+                launch_gemm<true>(Xrows, H, H, p.dZ, p.V_pad, V, Tcp, dW32, V, SPO_FP32, acc, p.n_act, t0, kLimitK, nullptr, s);
         }
     }
     if (need_acc) f32_to_bf16_kernel<<<grid1(V * H), 256, 0, s>>>(p.dW_acc, static_cast<bf16_t *>(d_W), V * H);
