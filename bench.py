@@ -169,7 +169,7 @@ def main() -> int:
         "config": {"workload": f"{cfg.name}: {B} packed responses, lengths {cfg.lengths}, T={T} tokens, "
                                f"H={H}, V={V}, {cfg.N}-prompt tracker, mask {cfg.mask_frac}",
                    "T": T, "B": B, "H": H, "V": V, "N": cfg.N, "eps": [cfg.eps_low, cfg.eps_high],
-                   "d_half": cfg.d_half, "chunk_tokens": args.chunk_tokens or 32768},
+                   "d_half": cfg.d_half, "chunk_tokens": args.chunk_tokens or 131072},
         "tflops_useful": round(3 * thv / sec / 1e12, 1),      # fwd + dHidden + dW
         "tflops_executed": round(4 * thv / sec / 1e12, 1),    # + the backward's recompute
         "mfma_util_executed": round(4 * thv / sec / 1e12 / PEAK_BF16_TFLOPS, 4),

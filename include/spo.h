@@ -226,9 +226,11 @@ int spo_pg_loss_fwd(const spo_pg_desc *d, float *loss, float *logp, float *lse, 
  *               needs d_W_dtype = SPO_FP32); 0: overwrite.
  * d_logits      [T, V] in desc dtype (logits-in form only).
  * chunk_tokens  tokens whose logit gradients are held in the workspace at once
- *               (0 picks a default).  The backward recomputes the logits tile by
- *               tile; a chunk's bf16 logit gradients live in the workspace
- *               between the three contractions, never the full [T x V].
+ *               (0 picks the default, 131072).  The backward recomputes the logits
+ *               tile by tile; a chunk's bf16 logit gradients (2 * V bytes per
+ *               token) live in the workspace between the three contractions,
+ *               never the full [T x V].  Fewer, larger chunks cost workspace and
+ *               save passes over d_W, which is read and rewritten once per chunk.
  * Tokens whose gradient factor is zero (masked, on the clipped branch, or in a
  * response with zero advantage) are left out of the recompute and of both
  * contractions: the cost of the backward follows the number of remaining tokens,

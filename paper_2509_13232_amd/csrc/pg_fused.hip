@@ -25,7 +25,9 @@ namespace spo {
 // than the same tile on 32x32x16 on the same chip: the instruction draws less power).
 typedef Tile<256, 256, 2, 4, 16> TL;
 constexpr int kSplitTerms = 6;    // cross products kept by the fp32 split
-constexpr int64_t kDefaultChunk = 32768;
+// tokens per backward chunk unless the caller says otherwise: 0.3 MB of bf16 logit gradients
+// per token at V = 151936, 40 GB per chunk; dW is read and rewritten once per chunk
+constexpr int64_t kDefaultChunk = 131072;
 
 // ----------------------------------------------------------------------------
 // operand preparation

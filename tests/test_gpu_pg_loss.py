@@ -99,6 +99,29 @@ def test_backward_chunks_and_output_dtypes(spo, oracle):
     assert rel_l2(f64(dx3), rb["d_hidden"]) < GRAD_TOL and rel_l2(f64(dw3), rb["d_W"]) < GRAD_TOL
 
 
+@pytest.mark.parametrize("w_layout", [0, 1])
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_head_gradient_on_ragged_shapes(spo, oracle, w_layout, dtype):
+    # dW contracts over tokens from rows of dZ and of the hidden states: a vocabulary that is
+    # neither a multiple of the tile nor of the 8-element pieces the rows are fetched in, a
+    # hidden size below one tile, a token count with a ragged last tile.  Element-wise check:
+    # a misplaced column or a piece fetched past the end of a row shows up in single entries.
+    say(f"fused {dtype} ragged T=300 H=192 V=1003 w_layout={w_layout}")
+    cfg = wl.scaled(MID, name="ragged", H=192, V=1003, dtype=dtype)
+    case = Case(cfg, [130, 170])
+    case.set_old_from_oracle(oracle)
+    fwd, dx, dw = run_fwd_bwd(spo, case, w_layout)
+    check_forward(case, oracle, fwd, atol_logp=2e-4 if dtype == "bf16" else 2e-5)
+    rb = oracle.pg_loss_bwd(*case.oracle_inputs(), *case.eps)
+    assert dw.shape == (1003, 192)
+    assert rel_l2(f64(dx), rb["d_hidden"]) < GRAD_TOL and rel_l2(f64(dw), rb["d_W"]) < GRAD_TOL
+    scale = np.abs(rb["d_W"]).max()
+    np.testing.assert_allclose(f64(dw), rb["d_W"], atol=2e-2 * scale, rtol=0)
+    # every vocabulary row's gradient against its own size (the target rows dominate the total)
+    rows = np.linalg.norm(f64(dw) - rb["d_W"], axis=1)
+    assert (rows <= 5e-2 * np.linalg.norm(rb["d_W"], axis=1) + 1e-3 * scale).all()
+
+
 @pytest.mark.parametrize("keep,chunk", [(256, 256), (257, 256), (1, 0), (300, 512), (511, 256)])
 def test_backward_runs_over_active_tokens_only(spo, oracle, keep, chunk):
     # A sparse loss mask: the backward gathers the tokens that carry a gradient and works on
