@@ -27,9 +27,11 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 # Bytes that crossed the L2 <-> fabric boundary per launch (reads + writes), from rocprofv3
 # FETCH_SIZE / WRITE_SIZE runs of this script at the default workload and chunk size, each
 # scaled by what the same counter reads for a plain 1 GiB copy (profiles/step_c3_hbm_traffic.md).
-# Valid only for the kernels as profiled: None for any other workload or chunk size.
+# Averages over all launches of a step (two full backward chunks and a short one), like the
+# launch time they are set against.  Valid only for the kernels as profiled: None for any
+# other workload or chunk size.
 TRAFFIC_BYTES_PER_LAUNCH = {
-    ("C3", 0): {"fwd_sweep": 764.4e9, "bwd_recompute": 84.8e9, "bwd_dhidden": 60.7e9, "bwd_dw": 74.7e9},
+    ("C3", 0): {"fwd_sweep": 809.6e9, "bwd_recompute": 217.9e9, "bwd_dhidden": 173.6e9, "bwd_dw": 226.4e9},
 }
 
 
