@@ -6,9 +6,11 @@
 //   backward  recomputes the logits tile by tile, turns them into bf16 logit
 //             gradients dZ for one chunk of tokens at a time, and contracts that
 //             chunk twice (dHidden = dZ W, dW += dZ^T X).
-// All contractions run through the one main loop of gemm_core.hpp in the form
-// D[m][n] = sum_k A[m][k] B[n][k]; small transposition kernels provide the
-// operands whose contraction index is not contiguous in the caller's layout.
+// The logits and dHidden run through the main loop of gemm_core.hpp in the form
+// D[m][n] = sum_k A[m][k] B[n][k] (a transposition kernel provides the head with
+// the vocabulary contiguous for dHidden); dW contracts over tokens, the row index
+// of both dZ and the hidden states, through the loop's second form
+// D[m][n] = sum_k A[k][m] B[k][n], so neither is copied.
 //
 // fp32 inputs use the same bf16 main loop: every value is split into three bf16
 // parts (x = x0 + x1 + x2) and the six leading cross products are laid side by
