@@ -24,6 +24,8 @@
 // (vocabulary entries) on m and the index with per-lane constants (tokens) on n.
 #pragma once
 
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace spo {
@@ -35,6 +37,7 @@ constexpr int kBK = 64;      // contraction elements per stage
 constexpr int kStages = 2;   // LDS stages
 constexpr int kRowBytes = kBK * 2;
 constexpr int kChunks = kRowBytes / 16;
+constexpr int kBlockK = kBK;  // contraction elements per block of a k-blocked operand: one stage
 
 // chunk swizzle of a tile row (3 bits): a bijection on 0..7 both over rows 0..7
 // and over the rows of equal parity in 0..15, i.e. 16 consecutive rows reading
@@ -97,13 +100,21 @@ struct Tile {
 
     // Global -> LDS transfers of one tile: addressing and issue.
     // Slot q = i*NT + tid of a tile <-> (row q/kChunks, position q%kChunks).
+    // An operand may be stored in blocks of kBlockK contraction elements: element k of row m at
+    // base + (k / kBlockK) * blk + m * ld + (k % kBlockK) * 2 bytes (blk = 0: plain row-major).
+    // With ld = 128 bytes a stage of a tile is then one contiguous 32 KiB piece instead of 256
+    // lines a whole matrix row apart: the 256 rows stay within a few pages of the address
+    // translation and spread evenly over the memory channels.
     struct Dma {
         const char *a_tile, *b_tile;     // first row of the A / B panel (wave-uniform)
+        int64_t a_blk, b_blk;            // bytes from one block of kBlockK contraction elements to the next
         uint32_t oa[A_LOADS], ob[B_LOADS];  // this lane's byte offsets inside the panels
         uint32_t lds_wave;               // LDS address of this wave's 1 KiB slice of stage 0
 
         __device__ __forceinline__ Dma(const char *A, int64_t lda_bytes, int64_t m0, int64_t M, const char *B,
-                                       int64_t ldb_bytes, int64_t n0, int64_t N, char *lds) {
+                                       int64_t ldb_bytes, int64_t n0, int64_t N, char *lds, int64_t a_blk_bytes,
+                                       int64_t b_blk_bytes)
+            : a_blk(a_blk_bytes ? a_blk_bytes : kBlockK * 2), b_blk(b_blk_bytes ? b_blk_bytes : kBlockK * 2) {
             const int tid = threadIdx.x;
             const int ld_row = tid / kChunks;
             const int ld_chunk = (tid % kChunks) ^ swz(ld_row & 15);
@@ -145,9 +156,9 @@ struct Tile {
         // DMA instruction i (0 .. STAGE_LOADS-1) of this thread's share of stage kt
         __device__ __forceinline__ void one(int kt, int i) const {
             const uint32_t la = lds_wave + (kt % kStages) * STAGE_BYTES;
-            const int64_t koff = static_cast<int64_t>(kt) * kRowBytes;
-            if (i < A_LOADS) dma(a_tile + koff, oa[i], la + i * (NT * 16));
-            else dma(b_tile + koff, ob[i - A_LOADS], la + A_BYTES + (i - A_LOADS) * (NT * 16));
+            static_assert(kBlockK == kBK, "one block per stage");
+            if (i < A_LOADS) dma(a_tile + kt * a_blk, oa[i], la + i * (NT * 16));
+            else dma(b_tile + kt * b_blk, ob[i - A_LOADS], la + A_BYTES + (i - A_LOADS) * (NT * 16));
         }
         __device__ __forceinline__ void stage(int kt) const {
 #pragma unroll
@@ -160,8 +171,8 @@ struct Tile {
     // stage0_issued = true.  All threads of the block must call this together.
     __device__ static __forceinline__ void prefetch(const char *__restrict__ A, int64_t lda_bytes, int64_t m0, int64_t M,
                                                     const char *__restrict__ B, int64_t ldb_bytes, int64_t n0, int64_t N,
-                                                    char *lds) {
-        const Dma d(A, lda_bytes, m0, M, B, ldb_bytes, n0, N, lds);
+                                                    char *lds, int64_t a_blk = 0, int64_t b_blk = 0) {
+        const Dma d(A, lda_bytes, m0, M, B, ldb_bytes, n0, N, lds, a_blk, b_blk);
         __syncthreads();  // every wave is done with the previous contents of lds
         d.stage(0);
     }
@@ -171,8 +182,9 @@ struct Tile {
     // 16-byte aligned.  All threads of the block must call this together.
     __device__ static __forceinline__ void mainloop(const char *__restrict__ A, int64_t lda_bytes, int64_t m0, int64_t M,
                                                     const char *__restrict__ B, int64_t ldb_bytes, int64_t n0, int64_t N,
-                                                    int KT, char *lds, Acc &acc, bool stage0_issued = false) {
-        mainloop16(A, lda_bytes, m0, M, B, ldb_bytes, n0, N, KT, lds, acc, stage0_issued);
+                                                    int KT, char *lds, Acc &acc, bool stage0_issued = false,
+                                                    int64_t a_blk = 0, int64_t b_blk = 0) {
+        mainloop16(A, lda_bytes, m0, M, B, ldb_bytes, n0, N, KT, lds, acc, stage0_issued, a_blk, b_blk);
     }
 
     // A lone wavefront cannot issue these four-pass MFMAs back to back, so
@@ -184,11 +196,12 @@ struct Tile {
     // four MFMAs).
     __device__ static __forceinline__ void mainloop16(const char *__restrict__ A, int64_t lda_bytes, int64_t m0, int64_t M,
                                                       const char *__restrict__ B, int64_t ldb_bytes, int64_t n0, int64_t N,
-                                                      int KT, char *lds, Acc &acc, bool stage0_issued) {
+                                                      int KT, char *lds, Acc &acc, bool stage0_issued, int64_t a_blk,
+                                                      int64_t b_blk) {
         static_assert(KK == 2 && kStages == 2, "two k-slices per stage, two stages");
         static_assert((FM + FN) * 2 <= FM * FN && STAGE_LOADS * 4 <= FM * FN, "reads and DMA fit between the MFMAs of a slice");
         const int lane = threadIdx.x & 63;
-        const Dma d(A, lda_bytes, m0, M, B, ldb_bytes, n0, N, lds);
+        const Dma d(A, lda_bytes, m0, M, B, ldb_bytes, n0, N, lds, a_blk, b_blk);
         // lane reads row (l%16) of a 16-row block, chunk 4*kk + l/16
         const int fr_sw = swz(lane & 15);
         int fr_off[KK];
@@ -220,7 +233,11 @@ struct Tile {
         fence_barrier();
 #pragma unroll
         for (int r = 0; r < FM + FN; ++r) read_frag(0, 0, 0, r);
-        for (int kt = 0; kt < KT; ++kt) {
+        // One step; MORE: a stage kt+1 exists, FEED: a stage kt+2 exists.  Compile-time flags: a
+        // branch around every read and every DMA instruction costs the wavefront more issue time
+        // than the instruction it guards, so the last two steps are peeled off the loop instead.
+        auto step = [&](int kt, auto more_t, auto feed_t) {
+            constexpr bool MORE = decltype(more_t)::value, FEED = decltype(feed_t)::value;
             // ---- slice 0 of stage kt, reading its slice 1 between the MFMAs
 #pragma unroll
             for (int j = 0; j < FM * FN; ++j) {
@@ -234,23 +251,26 @@ struct Tile {
             }
             asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
             fence_barrier();
-            const bool more = kt + 1 < KT, feed = kt + 2 < KT;
             // ---- slice 1, reading slice 0 of stage kt+1 and feeding the DMA of stage kt+2
 #pragma unroll
             for (int j = 0; j < FM * FN; ++j) {
                 const int fm = j / FN, fn = j % FN;
                 if (j % 2 == 0 && j / 2 < FM + FN) {
-                    if (more) read_frag(kt + 1, 0, 0, j / 2);
+                    if (MORE) read_frag(kt + 1, 0, 0, j / 2);
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 if (j % 4 == 1 && j / 4 < STAGE_LOADS) {
-                    if (feed) d.one(kt + 2, j / 4);
+                    if (FEED) d.one(kt + 2, j / 4);
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 acc[fm][fn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[1][fm], bf[1][fn], acc[fm][fn], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
-        }
+        };
+        int kt = 0;
+        for (; kt + 2 < KT; ++kt) step(kt, std::true_type{}, std::true_type{});
+        if (kt + 1 < KT) step(kt++, std::true_type{}, std::false_type{});
+        step(kt, std::false_type{}, std::false_type{});
     }
 
     // ---- operands with the contraction index as the ROW index: A[k][m], B[k][n] ----
@@ -274,9 +294,13 @@ struct Tile {
         uint32_t oa[K_LOADS], ob[K_LOADS];
         uint32_t lds_wave;
         // Mr, Nr: readable length of a row of A, B (multiples of 8 elements); chunks past it are
-        // fetched from the row's last readable chunk (the caller masks those columns)
+        // fetched from the row's last readable chunk (the caller masks those columns).
+        // a_sub / b_sub != 0: the operand's columns are stored in blocks of kBlockK (the k-blocked
+        // layout of Dma seen from the other side): column c of row k at
+        // base + (c / kBlockK) * sub + k * ld + (c % kBlockK) * 2 bytes, all BM (BN) columns readable.
         __device__ __forceinline__ DmaK(const char *A, int64_t lda_bytes, int64_t m0, int64_t Mr, const char *B,
-                                        int64_t ldb_bytes, int64_t n0, int64_t Nr, char *lds) {
+                                        int64_t ldb_bytes, int64_t n0, int64_t Nr, char *lds, int64_t a_sub,
+                                        int64_t b_sub) {
             const int tid = threadIdx.x;
             auto uniform = [](const char *p) {
                 const uint64_t u = reinterpret_cast<uint64_t>(p);
@@ -293,8 +317,11 @@ struct Tile {
 #pragma unroll
             for (int i = 0; i < K_LOADS; ++i) {
                 const int q = i * NT + tid, row = q / K_CH, c = (q % K_CH) ^ ksw(row);
-                oa[i] = static_cast<uint32_t>(row * lda_bytes + (c < a_last ? c : a_last) * 16);
-                ob[i] = static_cast<uint32_t>(row * ldb_bytes + (c < b_last ? c : b_last) * 16);
+                constexpr int cpb = kBlockK / 8;  // 16-byte chunks per block of columns
+                oa[i] = a_sub ? static_cast<uint32_t>((c / cpb) * a_sub + row * lda_bytes + (c % cpb) * 16)
+                              : static_cast<uint32_t>(row * lda_bytes + (c < a_last ? c : a_last) * 16);
+                ob[i] = b_sub ? static_cast<uint32_t>((c / cpb) * b_sub + row * ldb_bytes + (c % cpb) * 16)
+                              : static_cast<uint32_t>(row * ldb_bytes + (c < b_last ? c : b_last) * 16);
             }
             lds_wave = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char *)lds)) +
                        wave_id() * (kWave * 16);
@@ -319,7 +346,7 @@ struct Tile {
     // per lane that the MFMA wants (two reads per fragment, one read per MFMA while they last).
     __device__ static __forceinline__ void mainloop_kmajor(const char *__restrict__ A, int64_t lda_bytes, int64_t m0, int64_t Mr,
                                                            const char *__restrict__ B, int64_t ldb_bytes, int64_t n0, int64_t Nr,
-                                                           int KT, char *lds, Acc &acc) {
+                                                           int KT, char *lds, Acc &acc, int64_t a_sub = 0, int64_t b_sub = 0) {
         typedef short v4s __attribute__((ext_vector_type(4)));
         typedef short v8s __attribute__((ext_vector_type(8)));
         static_assert(KK == 2 && kStages == 2, "two k-slices per stage, two stages");
@@ -327,7 +354,7 @@ struct Tile {
         static_assert(NR <= FM * FN && STAGE_LOADS * 4 <= FM * FN, "reads and DMA fit between the MFMAs of a slice");
         static_assert((32 + 4) * K_ROWB < 65536, "slice and half offsets fit the read's offset field");
         const int lane = threadIdx.x & 63;
-        const DmaK d(A, lda_bytes, m0, Mr, B, ldb_bytes, n0, Nr, lds);
+        const DmaK d(A, lda_bytes, m0, Mr, B, ldb_bytes, n0, Nr, lds, a_sub, b_sub);
         const int G = lane >> 4, sl = lane & 15;
         // LDS address of this lane's source piece of a block, slice 0, first half, stage 0.  The
         // slice adds 32 rows and the half 4 rows (neither changes ksw); the stage is toggled in.
@@ -382,7 +409,8 @@ struct Tile {
         fence_barrier();
 #pragma unroll
         for (int r = 0; r < NR; ++r) read_half(0, 0, r);
-        for (int kt = 0; kt < KT; ++kt) {
+        auto step = [&](int kt, auto more_t, auto feed_t) {  // flags as in mainloop16
+            constexpr bool MORE = decltype(more_t)::value, FEED = decltype(feed_t)::value;
             // ---- slice 0 of stage kt, reading its slice 1 between the MFMAs
 #pragma unroll
             for (int j = 0; j < FM * FN; ++j) {
@@ -397,23 +425,26 @@ struct Tile {
             asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
             fence_barrier();
             other_stage();
-            const bool more = kt + 1 < KT, feed = kt + 2 < KT;
             // ---- slice 1, reading slice 0 of stage kt+1 and feeding the DMA of stage kt+2
 #pragma unroll
             for (int j = 0; j < FM * FN; ++j) {
                 const int fm = j / FN, fn = j % FN;
                 if (j < NR) {
-                    if (more) read_half(0, 0, j);
+                    if (MORE) read_half(0, 0, j);
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 if (j % 4 == 1 && j / 4 < STAGE_LOADS) {
-                    if (feed) d.one(kt + 2, j / 4);
+                    if (FEED) d.one(kt + 2, j / 4);
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 acc[fm][fn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(frag(ah[1][fm]), frag(bh[1][fn]), acc[fm][fn], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
-        }
+        };
+        int kt = 0;
+        for (; kt + 2 < KT; ++kt) step(kt, std::true_type{}, std::true_type{});
+        if (kt + 1 < KT) step(kt++, std::true_type{}, std::false_type{});
+        step(kt, std::false_type{}, std::false_type{});
     }
 
     __device__ static __forceinline__ void zero(Acc &acc) {

@@ -60,7 +60,9 @@ __device__ __forceinline__ bf16_t load_as_bf16(const bf16_t *p) { return *p; }
 __device__ __forceinline__ bf16_t load_as_bf16(const float *p) { return f32_to_bf16(*p); }
 
 // dst[c][r] = bf16(src[r][c]) for r < R, c < C; dst[c][r] = 0 for R <= r < R_pad and
-// for C <= c < C_pad (all r < R_pad).  dst has leading dimension ld_dst >= R_pad.
+// for C <= c < C_pad (all r < R_pad).  dst has leading dimension ld_dst >= R_pad, or with
+// ld_dst == 0 it is stored in blocks of kBlockK values of r (the layout the main loop reads
+// as a k-blocked operand): dst[c][r] at (r / kBlockK) * C_pad * kBlockK + c * kBlockK + r % kBlockK.
 template <typename SrcT>
 __global__ void __launch_bounds__(256)
 transpose_to_bf16_kernel(const SrcT *__restrict__ src, int64_t R, int64_t C, int64_t ld_src,
@@ -75,7 +77,8 @@ transpose_to_bf16_kernel(const SrcT *__restrict__ src, int64_t R, int64_t C, int
     __syncthreads();
     for (int i = ty; i < 64; i += 4) {
         const int64_t c = c0 + i, r = r0 + tx;
-        if (c < C_pad && r < R_pad) dst[c * ld_dst + r] = tile[tx][i];
+        if (c < C_pad && r < R_pad)
+            dst[ld_dst ? c * ld_dst + r : (r / kBlockK) * (C_pad * kBlockK) + c * kBlockK + r % kBlockK] = tile[tx][i];
     }
 }
 
@@ -304,18 +307,21 @@ fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const
 // ----------------------------------------------------------------------------
 // backward, step 1: recompute a logits tile and emit its bf16 gradient
 // ----------------------------------------------------------------------------
-// dz[t][v] = g[t] * ([v == target[t]] - exp(z[t][v] - lse[t])), written as
-// dZ[t][v] (row stride ldz, vocabulary contiguous): dHidden contracts it over v
-// and dW over t, both from this one copy.  Columns V <= v < V_pad of dZ and tokens
-// past T_valid are written as zeros.  Token tiles that start at or after the
+// dz[t][v] = g[t] * ([v == target[t]] - exp(z[t][v] - lse[t])), written once, in blocks
+// of kBlockK = 64 vocabulary entries: dz[t][v] at dZ + (v / 64) * dz_blk + t * 64 + v % 64
+// (dz_blk elements per block = rows of the chunk * 64).  A tile of this kernel is four
+// contiguous 32 KiB pieces.  dHidden reads the blocks as a k-blocked operand (contraction
+// over v: one block per k-step), dW reads four neighbouring blocks as a matrix with the
+// tokens as rows (contraction over t).  Entries with v >= V and tokens past T_valid are
+// written as zeros.  Token tiles that start at or after the
 // number of active rows of this chunk (device value n_act[0] - row_base) are
 // skipped altogether.
 __global__ void __launch_bounds__(TL::NT)
-recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, int64_t V_pad,
+recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V,
                     const char *__restrict__ X, int64_t ldx_bytes, int64_t T_valid, int KT,
                     const int32_t *__restrict__ target, const float *__restrict__ lse,
                     const float *__restrict__ g, int64_t nVt, int64_t nTt, bf16_t *__restrict__ dZ,
-                    int64_t ldz, const int32_t *__restrict__ n_act, int64_t row_base) {
+                    int64_t dz_blk, const int32_t *__restrict__ n_act, int64_t row_base) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     int64_t tm, tn;
     if (!TileOrder(nVt, nTt).tile(blockIdx.x, tm, tn)) return;
@@ -379,12 +385,14 @@ recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, in
     __syncthreads();
     // every wavefront writes 32 token rows, two rows (2 x 512 contiguous bytes) per store
     const int ci = lane & 31;  // 16-byte chunk of a row that this lane writes out
-    const bool col_ok = m0 + ci * 8 < V_pad;
+    static_assert(TL::BM % kBlockK == 0, "a vocabulary tile is a whole number of blocks of dZ");
+    constexpr int cpb = kBlockK / 8;  // 16-byte chunks per block row
+    bf16_t *piece = dZ + (tm * (TL::BM / kBlockK) + ci / cpb) * dz_blk + n0 * kBlockK + (ci % cpb) * 8;
 #pragma unroll
     for (int i = 0; i < TL::BN / TL::NWAVE / 2; ++i) {
         const int tl = TL::wave_id() * (TL::BN / TL::NWAVE) + 2 * i + (lane >> 5);
         const uint4 v = *reinterpret_cast<const uint4 *>(lds + tl * 512 + ((ci ^ (tl & 31)) << 4));
-        if (col_ok) *reinterpret_cast<uint4 *>(dZ + (n0 + tl) * ldz + m0 + ci * 8) = v;
+        *reinterpret_cast<uint4 *>(piece + tl * kBlockK) = v;
     }
 }
 
@@ -393,7 +401,11 @@ recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, in
 // ----------------------------------------------------------------------------
 // out[row(m)*ldo + n] (=|+=) sum_k A[m][k] B[n][k], or with KMajor
 // sum_k A[k][m] B[k][n] (rows of A and B are then readable up to the next multiple
-// of 8 elements past M and N).
+// of 8 elements past M and N).  An operand with a_blk / b_blk != 0 is stored in blocks
+// of kBlockK = 64 elements of its contiguous index, blk bytes apart, rows 128 bytes
+// apart inside a block: for the plain form that index is k (see Dma), for KMajor it is
+// m (n), and tile tm (tn) of the operand is made of the four blocks from 4 tm (4 tn) on
+// (see DmaK).
 // With n_act != NULL the extent that holds active tokens is read on the device
 // (rows = active_rows(n_act, row_base, .)): limit == kLimitRows keeps only the first
 // `rows` rows of A and stores row m at out row row_map[m] (dHidden: scatter back to the
@@ -406,8 +418,10 @@ __global__ void __launch_bounds__(TL::NT)
 gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, const char *__restrict__ B,
                   int64_t ldb_bytes, int64_t N, int KT, void *__restrict__ out, int64_t ldo, int out_dtype,
                   int accumulate, const int32_t *__restrict__ n_act, int64_t row_base, int limit,
-                  const int32_t *__restrict__ row_map) {
+                  const int32_t *__restrict__ row_map, int64_t a_blk, int64_t b_blk) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
+    constexpr int bpt = TL::BM / kBlockK;  // blocks per tile edge
+    static_assert(TL::BM % kBlockK == 0 && TL::BN == TL::BM, "a tile of a blocked operand is a whole number of blocks");
     int64_t tm, tn;
     if (!TileOrder(ceil_div(M, TL::BM), ceil_div(N, TL::BN)).tile(blockIdx.x, tm, tn)) return;
     const int64_t m0 = tm * TL::BM, n0 = tn * TL::BN;
@@ -424,8 +438,14 @@ gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, cons
     TL::Acc acc;
     TL::zero(acc);
     if (KT > 0) {
-        if (KMajor) TL::mainloop_kmajor(A, lda_bytes, m0, (M + 7) & ~int64_t(7), B, ldb_bytes, n0, (N + 7) & ~int64_t(7), KT, lds, acc);
-        else TL::mainloop(A, lda_bytes, m0, M, B, ldb_bytes, n0, N, KT, lds, acc);
+        if (KMajor) {
+            const int64_t Mr = (M + 7) & ~int64_t(7), Nr = (N + 7) & ~int64_t(7);
+            TL::mainloop_kmajor(a_blk ? A + tm * bpt * a_blk : A, lda_bytes, a_blk ? 0 : m0, a_blk ? TL::BM : Mr,
+                                b_blk ? B + tn * bpt * b_blk : B, ldb_bytes, b_blk ? 0 : n0, b_blk ? TL::BN : Nr, KT, lds,
+                                acc, a_blk, b_blk);
+        } else {
+            TL::mainloop(A, lda_bytes, m0, M, B, ldb_bytes, n0, N, KT, lds, acc, false, a_blk, b_blk);
+        }
     }
 #pragma unroll
     for (int fn = 0; fn < TL::FN; ++fn) {
@@ -562,7 +582,7 @@ int fused_fwd(const spo_pg_desc *d, float *loss, float *logp, float *lse, float 
 }
 
 struct BwdPlan {
-    int64_t Tc, V_pad, Kc, T_pad;
+    int64_t Tc, V_pad, V_blk, Kc, T_pad;  // V rounded up to a k-step (64) and to whole tiles (256)
     double *count;
     float *g, *dW_acc;
     bf16_t *WT, *Xb, *dZ, *Xs, *Ws, *Wvh;  // Xb: bf16 copy of the gathered rows of an fp32 hidden
@@ -580,6 +600,7 @@ static BwdPlan plan_bwd(const spo_pg_desc *d, int64_t chunk_tokens, void *ws, bo
     p.Tc = std::min(round_up(tc, TL::BN), Tmax);
     p.T_pad = Tmax;
     p.V_pad = round_up(d->V, kBK);
+    p.V_blk = round_up(d->V, TL::BM);
     p.Kc = d->dtype == SPO_FP32 ? kSplitTerms * d->H : d->H;
     Arena a(ws);
     p.count = a.take<double>(1);
@@ -590,8 +611,8 @@ static BwdPlan plan_bwd(const spo_pg_desc *d, int64_t chunk_tokens, void *ws, bo
     p.lse_c = a.take<float>(p.Tc);
     p.g_c = a.take<float>(p.Tc);
     p.Xc = a.take<char>(static_cast<size_t>(p.Tc) * d->H * (d->dtype == SPO_FP32 ? 4 : 2));
-    p.WT = a.take<bf16_t>(static_cast<size_t>(d->H) * p.V_pad);
-    p.dZ = a.take<bf16_t>(static_cast<size_t>(p.Tc) * p.V_pad);
+    p.WT = a.take<bf16_t>(static_cast<size_t>(d->H) * p.V_blk);   // [V_blk / 64][H][64]
+    p.dZ = a.take<bf16_t>(static_cast<size_t>(p.Tc) * p.V_blk);  // [V_blk / 64][rows of the chunk][64]
     p.Xb = p.Xs = p.Ws = p.Wvh = nullptr;
     p.dW_acc = nullptr;
     p.W32 = nullptr;
@@ -624,11 +645,12 @@ static void launch_transpose(const SrcT *src, int64_t R, int64_t C, int64_t ld_s
 template <bool KMajor>
 static void launch_gemm(const bf16_t *A, int64_t lda, int64_t M, const bf16_t *B, int64_t ldb, int64_t N, int64_t K,
                         void *out, int64_t ldo, int out_dtype, int accumulate, const int32_t *n_act, int64_t row_base,
-                        int limit, const int32_t *row_map, hipStream_t s) {
+                        int limit, const int32_t *row_map, int64_t a_blk_elems, int64_t b_blk_elems, hipStream_t s) {
     const TileOrder ord(ceil_div(M, TL::BM), ceil_div(N, TL::BN));
     gemm_store_kernel<KMajor><<<static_cast<unsigned>(ord.blocks()), TL::NT, TL::LDS_BYTES, s>>>(
         reinterpret_cast<const char *>(A), lda * 2, M, reinterpret_cast<const char *>(B), ldb * 2, N,
-        static_cast<int>(K / kBK), out, ldo, out_dtype, accumulate, n_act, row_base, limit, row_map);
+        static_cast<int>(K / kBK), out, ldo, out_dtype, accumulate, n_act, row_base, limit, row_map, a_blk_elems * 2,
+        b_blk_elems * 2);
 }
 
 int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float grad_loss, void *d_hidden,
@@ -664,7 +686,7 @@ int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float g
         }
         split_expand_kernel<<<grid1(V * H), 256, 0, s>>>(w32, V, H, p.Ws, 0);
         Wk = p.Ws;
-        if (d_hidden) launch_transpose(w32, V, H, H, p.WT, p.V_pad, H, p.V_pad, s);
+        if (d_hidden) launch_transpose(w32, V, H, H, p.WT, p.V_blk, H, 0, s);
     } else {
         const bf16_t *Wvh = static_cast<const bf16_t *>(d->W);
         if (d->w_layout == SPO_W_HV) {
@@ -672,7 +694,7 @@ int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float g
             Wvh = p.Wvh;
         }
         Wk = Wvh;
-        if (d_hidden) launch_transpose(Wvh, V, H, H, p.WT, p.V_pad, H, p.V_pad, s);
+        if (d_hidden) launch_transpose(Wvh, V, H, H, p.WT, p.V_blk, H, 0, s);
     }
     // the tokens that carry a gradient, in order; the chunks below run over this list
     compact_active_kernel<<<1, 1024, 0, s>>>(p.g, T, p.act_idx, p.n_act);
@@ -706,23 +728,26 @@ int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float g
             const TileOrder ord(nVt, Tcp / TL::BN);
             ScopedKernelTimer timer(kTimeRecompute, s);
             recompute_dz_kernel<<<static_cast<unsigned>(ord.blocks()), TL::NT, TL::LDS_BYTES, s>>>(
-                reinterpret_cast<const char *>(Wk), p.Kc * 2, V, p.V_pad, reinterpret_cast<const char *>(Xk), p.Kc * 2,
+                reinterpret_cast<const char *>(Wk), p.Kc * 2, V, reinterpret_cast<const char *>(Xk), p.Kc * 2,
                 Tcp, static_cast<int>(p.Kc / kBK), p.tgt_c, p.lse_c, p.g_c, nVt, Tcp / TL::BN,
-                p.dZ, p.V_pad, p.n_act, t0);
+                p.dZ, Tcp * kBlockK, p.n_act, t0);
         }
         if (d_hidden) {
             ScopedKernelTimer timer(kTimeDHidden, s);
-            launch_gemm<false>(p.dZ, p.V_pad, Tcp, p.WT, p.V_pad, H, p.V_pad, d_hidden, H, d_hidden_dtype, 0, p.n_act, t0,
-                        kLimitRows, p.act_idx + t0, s);
+            // both operands k-blocked over the vocabulary: a stage of a tile is 32 KiB contiguous
+            launch_gemm<false>(p.dZ, kBlockK, Tcp, p.WT, kBlockK, H, p.V_pad, d_hidden, H, d_hidden_dtype, 0, p.n_act, t0,
+                               kLimitRows, p.act_idx + t0, Tcp * kBlockK, H * kBlockK, s);
         }
         if (d_W) {
             const int acc = (c > 0 || accumulate_dW) ? 1 : 0;
             ScopedKernelTimer timer(kTimeDW, s);
             // contraction over the chunk's tokens, the row index of both dZ and the gathered hidden rows
             if (d->w_layout == SPO_W_VH)
-                launch_gemm<true>(p.dZ, p.V_pad, V, Xrows, H, H, Tcp, dW32, H, SPO_FP32, acc, p.n_act, t0, kLimitK, nullptr, s);
+                launch_gemm<true>(p.dZ, kBlockK, V, Xrows, H, H, Tcp, dW32, H, SPO_FP32, acc, p.n_act, t0, kLimitK, nullptr,
+                                  Tcp * kBlockK, 0, s);
             else
-                launch_gemm<true>(Xrows, H, H, p.dZ, p.V_pad, V, Tcp, dW32, V, SPO_FP32, acc, p.n_act, t0, kLimitK, nullptr, s);
+                launch_gemm<true>(Xrows, H, H, p.dZ, kBlockK, V, Tcp, dW32, V, SPO_FP32, acc, p.n_act, t0, kLimitK, nullptr,
+                                  0, Tcp * kBlockK, s);
         }
     }
     if (need_acc) f32_to_bf16_kernel<<<grid1(V * H), 256, 0, s>>>(p.dW_acc, static_cast<bf16_t *>(d_W), V * H);
