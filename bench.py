@@ -31,7 +31,7 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 # launch time they are set against.  Valid only for the kernels as profiled: None for any
 # other workload or chunk size.
 TRAFFIC_BYTES_PER_LAUNCH = {
-    ("C3", 0): {"fwd_sweep": 809.6e9, "bwd_recompute": 217.9e9, "bwd_dhidden": 173.6e9, "bwd_dw": 226.4e9},
+    ("C3", 0): {"fwd_sweep": 753.2e9, "bwd_recompute": 205.2e9, "bwd_dhidden": 174.2e9, "bwd_dw": 236.3e9},
 }
 
 
@@ -143,7 +143,12 @@ def main() -> int:
         f"mean ratio {stats[2]:.4f}")
 
     # ---------------------------------------------------------------- roofline of the dominant kernel
-    thv = 2.0 * T * H * V   # flops of one [T x H] x [H x V] contraction
+    # The forward contracts over all T tokens; the backward only over the tokens that carry a
+    # gradient (unmasked and on the unclipped branch: stats[0] * (1 - stats[1]) of them).
+    t_active = round(stats[0] * (1.0 - stats[1]))
+    thv = {"fwd_sweep": 2.0 * T * H * V}            # flops of one contraction of a kernel class per step
+    for name in ("bwd_recompute", "bwd_dhidden", "bwd_dw"):
+        thv[name] = 2.0 * t_active * H * V
     kern = {}
     for name in ("fwd_sweep", "bwd_recompute", "bwd_dhidden", "bwd_dw"):
         ms, n = times[name]
@@ -151,10 +156,10 @@ def main() -> int:
             per_step_ms = ms / args.steps
             kern[name] = {"ms_per_step": round(per_step_ms, 3), "launches_per_step": n // args.steps,
                           "avg_launch_ms": round(ms / n, 4),
-                          "tflops": round(thv / (per_step_ms * 1e-3) / 1e12, 1)}
+                          "tflops": round(thv[name] / (per_step_ms * 1e-3) / 1e12, 1)}
     dom = max(kern, key=lambda k: kern[k]["ms_per_step"])
     ms_dom, n_dom = times[dom]
-    flops_per_launch = thv * args.steps / n_dom
+    flops_per_launch = thv[dom] * args.steps / n_dom
     achieved = flops_per_launch / (ms_dom / n_dom * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
@@ -172,9 +177,10 @@ def main() -> int:
                                f"H={H}, V={V}, {cfg.N}-prompt tracker, mask {cfg.mask_frac}",
                    "T": T, "B": B, "H": H, "V": V, "N": cfg.N, "eps": [cfg.eps_low, cfg.eps_high],
                    "d_half": cfg.d_half, "chunk_tokens": args.chunk_tokens or 131072},
-        "tflops_useful": round(3 * thv / sec / 1e12, 1),      # fwd + dHidden + dW
-        "tflops_executed": round(4 * thv / sec / 1e12, 1),    # + the backward's recompute
-        "mfma_util_executed": round(4 * thv / sec / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "active_tokens": t_active,
+        "tflops_useful": round((thv["fwd_sweep"] + thv["bwd_dhidden"] + thv["bwd_dw"]) / sec / 1e12, 1),
+        "tflops_executed": round(sum(thv.values()) / sec / 1e12, 1),    # + the backward's recompute
+        "mfma_util_executed": round(sum(thv.values()) / sec / 1e12 / PEAK_BF16_TFLOPS, 4),
         "clipped_share": round(stats[1], 5),
         "device": torch.cuda.get_device_name(0), "torch": torch.__version__,
         "roofline": roofline,
