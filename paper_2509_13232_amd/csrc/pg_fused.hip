@@ -27,6 +27,7 @@ namespace spo {
 // than the same tile on 32x32x16 on the same chip: the instruction draws less power).
 typedef Tile<256, 256, 2, 4, 16> TL;
 constexpr int kSplitTerms = 6;    // cross products kept by the fp32 split
+constexpr int kSweepSplits = 16;  // vocabulary splits of the forward sweep on large problems (a multiple of 8)
 // tokens per backward chunk unless the caller says otherwise: 0.3 MB of bf16 logit gradients
 // per token at V = 151936, 40 GB per chunk; dW is read and rewritten once per chunk
 constexpr int64_t kDefaultChunk = 131072;
@@ -193,8 +194,11 @@ gather_chunk_kernel(const T_ *__restrict__ X, int64_t H, const int32_t *__restri
 // Tile rows (m) are vocabulary entries, tile columns (n) are tokens, so that each
 // lane owns FN tokens and reduces over the vocabulary inside its own registers.
 // Workgroup (token tile jt, vocabulary split r) walks the vocabulary tiles of its
-// split; ids equal mod 8 (same XCD, same L2) hold the splits of the same few
-// token tiles, which then share hidden-state panels in that L2.
+// split.  Ids equal mod 8 run on the same XCD and share its L2: there, 32 consecutive
+// workgroups are a patch of 4 token tiles x 8 splits (each hidden-state panel feeds 8
+// of them, each head tile 4), and the patches of one group of 4 token tiles follow
+// one another.  More than 8 splits shorten a workgroup's sweep: workgroups that share
+// lines then have less time to drift apart before new ones start in step.
 __global__ void __launch_bounds__(TL::NT)
 fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const char *__restrict__ X,
                  int64_t ldx_bytes, int64_t T, int KT, const int32_t *__restrict__ target, int nsplit,
@@ -202,8 +206,17 @@ fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const
                  float *__restrict__ part_sum, float *__restrict__ z_target) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int64_t bid = blockIdx.x, xcd = bid & 7, q = bid >> 3;
-    const int split = static_cast<int>(q % nsplit);
-    const int64_t jt = (q / nsplit) * 8 + xcd;
+    int split;
+    int64_t jt;
+    if (nsplit % 8 == 0) {
+        const int groups = nsplit / 8, w = static_cast<int>(q & 31);
+        const int64_t patch = q >> 5;
+        split = static_cast<int>(patch % groups) * 8 + (w & 7);
+        jt = ((patch / groups) * 4 + (w >> 3)) * 8 + xcd;
+    } else {  // small problems: all splits of a token tile side by side
+        split = static_cast<int>(q % nsplit);
+        jt = (q / nsplit) * 8 + xcd;
+    }
     if (jt >= nTt) return;
     const int64_t n0 = jt * TL::BN;
     const int64_t vt0 = split * nVt / nsplit, vt1 = (split + 1) * nVt / nsplit;
@@ -507,7 +520,7 @@ static FwdPlan plan_fwd(const spo_pg_desc *d, void *ws) {
     p.nTt = ceil_div(d->T, TL::BN);
     p.nVt = ceil_div(d->V, TL::BM);
     p.T_pad = p.nTt * TL::BN;
-    int64_t ns = std::max<int64_t>(8, ceil_div(2048, std::max<int64_t>(p.nTt, 1)));
+    int64_t ns = std::max<int64_t>(kSweepSplits, ceil_div(2048, std::max<int64_t>(p.nTt, 1)));
     p.nsplit = static_cast<int>(std::min<int64_t>(ns, p.nVt));
     p.Kc = d->dtype == SPO_FP32 ? kSplitTerms * d->H : d->H;
     p.nblk_tok = ceil_div(std::max<int64_t>(d->T, 1), kTokThreads);
@@ -568,7 +581,9 @@ int fused_fwd(const spo_pg_desc *d, float *loss, float *logp, float *lse, float 
                 W = static_cast<const char *>(d->W);
             }
         }
-        const int64_t blocks = ceil_div(p.nTt, 8) * 8 * p.nsplit;
+        // token tiles per XCD, in whole patches of 4 when the splits come in groups of 8
+        const int64_t per_xcd = p.nsplit % 8 == 0 ? round_up(ceil_div(p.nTt, 8), 4) : ceil_div(p.nTt, 8);
+        const int64_t blocks = per_xcd * 8 * p.nsplit;
         ScopedKernelTimer timer(kTimeFwdSweep, s);
         fwd_sweep_kernel<<<static_cast<unsigned>(blocks), TL::NT, TL::LDS_BYTES, s>>>(
             W, p.Kc * 2, d->V, X, p.Kc * 2, d->T, static_cast<int>(p.Kc / kBK), d->target, p.nsplit, p.nTt, p.nVt,
