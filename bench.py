@@ -31,7 +31,7 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 # launch time they are set against.  Valid only for the kernels as profiled: None for any
 # other workload or chunk size.
 TRAFFIC_BYTES_PER_LAUNCH = {
-    ("C3", 0): {"fwd_sweep": 753.2e9, "bwd_recompute": 205.2e9, "bwd_dhidden": 174.2e9, "bwd_dw": 236.3e9},
+    ("C3", 0): {"fwd_sweep": 783.3e9, "bwd_recompute": 205.8e9, "bwd_dhidden": 175.1e9, "bwd_dw": 283.2e9},
 }
 
 
