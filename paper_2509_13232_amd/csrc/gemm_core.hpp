@@ -4,7 +4,7 @@
 // operands are row-major with the contraction index contiguous (mainloop: logits =
 // W h and dHidden = dZ W), or of  D[m][n] = sum_k A[k][m] * B[k][n]  where the
 // contraction index is the row index of both (mainloop_kmajor: dW = dZ^T X, which
-// contracts over tokens, read from the same token-major dZ and hidden rows).  The two
+// contracts over tokens: the rows of the hidden states and of the blocks of dZ).  The two
 // loops share the tile shape, the schedule and the accumulator layout.
 //
 // Data path per stage of 64 contraction elements (128 bytes = one cache line per
@@ -187,10 +187,10 @@ struct Tile {
         mainloop16(A, lda_bytes, m0, M, B, ldb_bytes, n0, N, KT, lds, acc, stage0_issued, a_blk, b_blk);
     }
 
-    // A lone wavefront cannot issue these four-pass MFMAs back to back, so
-    // the two wavefronts of a SIMD multiply at the same time and each hides its own fragment
-    // reads between its MFMAs (one read per two MFMAs, into a second register set for the next
-    // k-slice of 32).  One barrier per step, between the two k-slices: before it a wavefront has
+    // Both wavefronts of a SIMD multiply at the same time and each hides its own fragment reads
+    // between its MFMAs (one read per two MFMAs, into a second register set for the next
+    // k-slice of 32); whenever one of them waits, at the barrier or for its operands, the
+    // other keeps the MFMA pipe fed.  One barrier per step, between the two k-slices: before it a wavefront has
     // all its reads of stage s in registers and its share of stage s+1 landed; after it stage s+1
     // may be read and the buffer of stage s is refilled with stage s+2 (one DMA instruction per
     // four MFMAs).
