@@ -122,6 +122,34 @@ def test_head_gradient_on_ragged_shapes(spo, oracle, w_layout, dtype):
     assert (rows <= 5e-2 * np.linalg.norm(rb["d_W"], axis=1) + 1e-3 * scale).all()
 
 
+@pytest.mark.parametrize("lengths,V,H,w_layout,chunk", [
+    ([1], 5, 64, 0, 0),              # one token, vocabulary below one fetch piece
+    ([1], 5, 64, 1, 0),
+    ([200, 55], 63, 128, 1, 0),      # one short of a k-block of the vocabulary, one short of a token tile
+    ([129, 128], 65, 64, 0, 256),    # one past both, two chunks
+    ([500, 12], 1023, 192, 1, 256),  # one short of four vocabulary tiles
+    ([150, 150], 2049, 256, 0, 0),   # one past eight vocabulary tiles
+    ([40], 300, 320, 1, 0),          # hidden size between one and two tiles
+])
+def test_corner_shapes_match_oracle(spo, oracle, lengths, V, H, w_layout, chunk):
+    # sizes that sit on, just below and just above the tile, block and fetch-piece boundaries of
+    # the contraction kernels, forward and both gradients against the oracle
+    say(f"fused bf16 corner T={sum(lengths)} H={H} V={V} w_layout={w_layout} chunk={chunk}")
+    cfg = wl.scaled(MID, name="corner", H=H, V=V)
+    case = Case(cfg, lengths)
+    case.set_old_from_oracle(oracle)
+    fwd, dx, dw = run_fwd_bwd(spo, case, w_layout, chunk_tokens=chunk)
+    check_forward(case, oracle, fwd)
+    rb = oracle.pg_loss_bwd(*case.oracle_inputs(), *case.eps)
+    assert dw.shape == (V, H) and dx.shape == (sum(lengths), H)
+    if np.any(rb["d_hidden"]):
+        assert rel_l2(f64(dx), rb["d_hidden"]) < GRAD_TOL and rel_l2(f64(dw), rb["d_W"]) < GRAD_TOL
+        scale = np.abs(rb["d_W"]).max()
+        np.testing.assert_allclose(f64(dw), rb["d_W"], atol=2e-2 * scale, rtol=0)
+    else:   # every token ended on the clipped branch
+        assert not dx.any() and not dw.any()
+
+
 @pytest.mark.parametrize("keep,chunk", [(256, 256), (257, 256), (1, 0), (300, 512), (511, 256)])
 def test_backward_runs_over_active_tokens_only(spo, oracle, keep, chunk):
     # A sparse loss mask: the backward gathers the tokens that carry a gradient and works on
