@@ -88,6 +88,23 @@ int spo_sample_prompts(const float *alpha, const float *beta, int64_t N, int32_t
                        uint32_t max_attempts, int32_t *idx_out, int32_t *info, void *ws,
                        size_t ws_bytes, spo_stream_t stream);
 
+/* The same draw for callers that cannot allocate device memory or carry a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Arguments, result and errors are those of spo_sample_prompts
+ * without ws / ws_bytes; the CDF, the block sums and the owner table live in a
+ * fixed array of about 12.6 MB in device memory that belongs to the library (one
+ * copy per GPU, held until the process ends).  The call allocates nothing; its
+ * first call on a device looks the array's address up once.
+ * Limit: N <= SPO_SAMPLE_STATIC_MAX_N, otherwise SPO_ERANGE.
+ * Every call on a GPU uses that GPU's one array: calls that overlap in time on
+ * one GPU (different streams, different threads) race; order them.  Nothing has
+ * to be cleared between calls: each call rewrites what it reads. */
+#define SPO_SAMPLE_STATIC_MAX_N (1 << 20)
+int spo_sample_prompts_static(const float *alpha, const float *beta, int64_t N, int32_t B,
+                              double eps_explore, uint64_t seed, uint64_t iteration, int replace,
+                              uint32_t max_attempts, int32_t *idx_out, int32_t *info,
+                              spo_stream_t stream);
+
 /* ---------------------------------------------------------------------------
  * Advantages (Method, "Advantage Estimation and Policy Optimization": the raw
  * advantage A = r - v_{-1} with the PRE-update tracker mean as baseline, and the

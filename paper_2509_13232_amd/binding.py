@@ -16,9 +16,11 @@ LIB_PATH = os.path.join(_HERE, "libspo_hip.so")
 
 SPO_FP32, SPO_BF16 = 0, 1
 SPO_W_VH, SPO_W_HV = 0, 1
+SPO_SAMPLE_STATIC_MAX_N = 1 << 20
 
 EXPORTS = (
     "spo_status_string", "spo_sample_prompts_workspace_bytes", "spo_sample_prompts",
+    "spo_sample_prompts_static",
     "spo_advantages", "spo_advantage_diagnostics", "spo_tracker_update", "spo_tracker_update_ema",
     "spo_tracker_init",
     "spo_pg_loss_fwd_workspace_bytes", "spo_pg_loss_fwd",
@@ -65,6 +67,8 @@ def lib():
         L.spo_sample_prompts_workspace_bytes.argtypes = [i64, i32]
         L.spo_sample_prompts.restype = C.c_int
         L.spo_sample_prompts.argtypes = [vp, vp, i64, i32, f64, u64, u64, C.c_int, u32, vp, vp, vp, sz, vp]
+        L.spo_sample_prompts_static.restype = C.c_int
+        L.spo_sample_prompts_static.argtypes = [vp, vp, i64, i32, f64, u64, u64, C.c_int, u32, vp, vp, vp]
         L.spo_advantages.restype = C.c_int
         L.spo_advantages.argtypes = [vp, vp, i64, vp, vp, i32, C.c_int, f32, C.c_int, vp, vp, vp, vp]
         L.spo_advantage_diagnostics.restype = C.c_int
@@ -157,6 +161,23 @@ def spo_sample_prompts(alpha, beta, B, eps_explore=0.05, seed=0, iteration=0, re
                                     int(iteration), int(bool(replace)), int(max_attempts), _ptr(idx),
                                     _ptr(info), _ptr(ws), ws.numel(), _stream()), "spo_sample_prompts")
     return (idx, info) if return_info else idx
+
+
+def spo_sample_prompts_static(alpha, beta, B, eps_explore=0.05, seed=0, iteration=0, replace=False,
+                              max_attempts=0, idx_out=None, info_out=None):
+    """spo_sample_prompts without a workspace (the library's own fixed scratch array).  With
+    idx_out / info_out given, the call touches no allocator at all."""
+    N = alpha.numel()
+    _want(alpha, torch.float32, "alpha")
+    _want(beta, torch.float32, "beta", N)
+    idx = torch.empty(B, dtype=torch.int32, device=alpha.device) if idx_out is None else idx_out
+    info = torch.zeros(2, dtype=torch.int32, device=alpha.device) if info_out is None else info_out
+    _want(idx, torch.int32, "idx_out", B)
+    _want(info, torch.int32, "info_out", 2)
+    _check(lib().spo_sample_prompts_static(_ptr(alpha), _ptr(beta), N, B, float(eps_explore), int(seed),
+                                           int(iteration), int(bool(replace)), int(max_attempts), _ptr(idx),
+                                           _ptr(info), _stream()), "spo_sample_prompts_static")
+    return idx, info
 
 
 # --------------------------------------------------------------- advantages

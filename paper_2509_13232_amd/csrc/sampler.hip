@@ -7,6 +7,8 @@
 // rounded IEEE fp64 operation (add, divide, subtract, multiply, sqrt: no fused
 // multiply-add can form because no product feeds an addition), so the indices do
 // not depend on the machine, the launch shape or the order of summation.
+#include <mutex>
+
 #include "common.hpp"
 
 namespace spo {
@@ -272,21 +274,12 @@ extern "C" size_t spo_sample_prompts_workspace_bytes(int64_t N, int32_t B) {
     return sampler_layout(nullptr, N).bytes;
 }
 
-extern "C" int spo_sample_prompts(const float *alpha, const float *beta, int64_t N, int32_t B,
-                                  double eps_explore, uint64_t seed, uint64_t iteration, int replace,
-                                  uint32_t max_attempts, int32_t *idx_out, int32_t *info, void *ws,
-                                  size_t ws_bytes, spo_stream_t stream) {
-    if (!alpha || !beta || !idx_out) return SPO_ENULL;
-    if (N < 1 || N >= (int64_t(1) << 31) || B < 1 || !(eps_explore >= 0.0) || !(eps_explore <= 1.0))
-        return SPO_EINVAL;
-    if (!replace && B > N) return SPO_EINVAL;
-    if (!replace && B > kMaxSlotsNoReplace) return SPO_ERANGE;
-    if (!ws) return SPO_EWORKSPACE;
-    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return SPO_EINVAL;
+// Checks and launches shared by the two entry points; ws holds sampler_layout(ws, N).
+static int sample_launch(const float *alpha, const float *beta, int64_t N, int32_t B, double eps_explore,
+                         uint64_t seed, uint64_t iteration, int replace, uint32_t max_attempts,
+                         int32_t *idx_out, int32_t *info, void *ws, hipStream_t s) {
     const SamplerWorkspace w = sampler_layout(ws, N);
-    if (ws_bytes < w.bytes) return SPO_EWORKSPACE;
     if (max_attempts == 0) max_attempts = 1u << 20;
-    hipStream_t s = as_stream(stream);
     const int64_t nblocks = ceil_div(N, kScanItems);
     weight_block_sums_kernel<<<static_cast<unsigned>(nblocks), kScanThreads, 0, s>>>(alpha, beta, N, eps_explore, w.block_sums);
     scan_block_sums_kernel<<<1, kScanThreads, 0, s>>>(w.block_sums, nblocks, w.total);
@@ -299,4 +292,76 @@ extern "C" int spo_sample_prompts(const float *alpha, const float *beta, int64_t
                                                                      idx_out, info, w.owner);
     }
     return launch_status();
+}
+
+static int sample_check(const float *alpha, const float *beta, int64_t N, int32_t B, double eps_explore,
+                        int replace, const int32_t *idx_out) {
+    if (!alpha || !beta || !idx_out) return SPO_ENULL;
+    if (N < 1 || N >= (int64_t(1) << 31) || B < 1 || !(eps_explore >= 0.0) || !(eps_explore <= 1.0))
+        return SPO_EINVAL;
+    if (!replace && B > N) return SPO_EINVAL;
+    if (!replace && B > kMaxSlotsNoReplace) return SPO_ERANGE;
+    return SPO_OK;
+}
+
+extern "C" int spo_sample_prompts(const float *alpha, const float *beta, int64_t N, int32_t B,
+                                  double eps_explore, uint64_t seed, uint64_t iteration, int replace,
+                                  uint32_t max_attempts, int32_t *idx_out, int32_t *info, void *ws,
+                                  size_t ws_bytes, spo_stream_t stream) {
+    const int rc = sample_check(alpha, beta, N, B, eps_explore, replace, idx_out);
+    if (rc) return rc;
+    if (!ws) return SPO_EWORKSPACE;
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return SPO_EINVAL;
+    if (ws_bytes < sampler_layout(nullptr, N).bytes) return SPO_EWORKSPACE;
+    return sample_launch(alpha, beta, N, B, eps_explore, seed, iteration, replace, max_attempts, idx_out, info, ws,
+                         as_stream(stream));
+}
+
+// ----------------------------------------------------------------------------
+// The same draw for callers that cannot allocate: the CDF, the block sums and the
+// owner table live in a fixed array in device memory that belongs to the library
+// (one copy per GPU, held until the process ends).
+// ----------------------------------------------------------------------------
+namespace spo {
+
+constexpr int64_t kStaticMaxN = SPO_SAMPLE_STATIC_MAX_N;
+// what sampler_layout takes for kStaticMaxN prompts: 8 B (CDF) + 4 B (owner) per prompt,
+// one 8-byte sum per 4096 prompts, the total, each block rounded up to 256 bytes
+constexpr size_t kStaticBytes = static_cast<size_t>(kStaticMaxN) * 12 + (kStaticMaxN / kScanItems + 1) * 8 + 4 * 256;
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+// Device address of `scratch` on the current device.  In host code the array's name is only a
+// handle for hipGetSymbolAddress; every GPU has its own copy at its own address, looked up
+// once per device with that device current.
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static void *g_scratch_ptr[kMaxDevices];
+
+static int static_scratch(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SPO_EHIP;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SPO_EHIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return SPO_OK;
+}
+
+}  // namespace spo
+
+extern "C" int spo_sample_prompts_static(const float *alpha, const float *beta, int64_t N, int32_t B,
+                                         double eps_explore, uint64_t seed, uint64_t iteration, int replace,
+                                         uint32_t max_attempts, int32_t *idx_out, int32_t *info,
+                                         spo_stream_t stream) {
+    int rc = sample_check(alpha, beta, N, B, eps_explore, replace, idx_out);
+    if (rc) return rc;
+    if (N > kStaticMaxN) return SPO_ERANGE;  // the fixed array holds the tables of at most this many prompts
+    if (sampler_layout(nullptr, N).bytes > kStaticBytes) return SPO_ERANGE;
+    void *ws = nullptr;
+    if ((rc = static_scratch(&ws))) return rc;
+    return sample_launch(alpha, beta, N, B, eps_explore, seed, iteration, replace, max_attempts, idx_out, info, ws,
+                         as_stream(stream));
 }
