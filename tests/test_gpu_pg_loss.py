@@ -150,6 +150,49 @@ def test_corner_shapes_match_oracle(spo, oracle, lengths, V, H, w_layout, chunk)
         assert not dx.any() and not dw.any()
 
 
+DEEP = wl.scaled(wl.CONFIGS["C2"], name="deep", H=320, V=1100)
+DEEP_LENGTHS = [9000, 7000, 12001, 5000, 6999]  # T = 40000: 157 token tiles, three chunks of 16384
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("w_layout,w_scale", [(0, 1.0), (1, 1.0), (0, 30.0)])
+def test_dense_deep_token_contraction_of_dW(spo, oracle, w_layout, w_scale):
+    # The head gradient contracts over tokens.  Here nothing is masked, so every chunk of 16384
+    # tokens is one launch with 256 steps of the contraction, and the three chunks add into the
+    # same fp32 d_W (read-modify-write across launches), as in the benchmark configuration.
+    # Every entry of d_W and d_hidden is compared with the oracle; the softmax part of d_W
+    # (d_W minus the rank-one terms of the sampled tokens) is compared on its own, because with
+    # flat logits it hides inside the total; w_scale = 30 makes it as large as the target part.
+    say(f"fused bf16 deep T=40000 H=320 V=1100 chunk=16384 w_layout={w_layout} w_scale={w_scale}")
+    case = Case(DEEP, DEEP_LENGTHS, w_scale=w_scale)
+    assert case.T == 40000 and case.mask is None
+    case.set_old_from_oracle(oracle)
+    fwd, dx, dw = run_fwd_bwd(spo, case, w_layout, chunk_tokens=16384)
+    ref = check_forward(case, oracle, fwd)
+    assert ref["active"].sum() > 2 * 16384                   # three chunks of active tokens
+    rb = oracle.pg_loss_bwd(*case.oracle_inputs(), *case.eps)
+    got_dw, got_dx = f64(dw), f64(dx)
+    assert rel_l2(got_dx, rb["d_hidden"]) < GRAD_TOL and rel_l2(got_dw, rb["d_W"]) < GRAD_TOL
+    scale = np.abs(rb["d_W"]).max()
+    np.testing.assert_allclose(got_dw, rb["d_W"], atol=2e-2 * scale, rtol=0)
+    rows = np.linalg.norm(got_dw - rb["d_W"], axis=1)        # no vocabulary row hides in the norm
+    assert (rows <= 2 * GRAD_TOL * np.linalg.norm(rb["d_W"], axis=1) + 1e-3 * scale).all()
+    # softmax part: subtract sum over the tokens that sampled v of g_t h_t
+    g, Hd = rb["g"], f64(case.hidden)
+    onehot_dw = np.zeros_like(rb["d_W"])
+    np.add.at(onehot_dw, case.target, g[:, None] * Hd)
+    soft_ref, soft_gpu = rb["d_W"] - onehot_dw, got_dw - onehot_dw
+    # bf16 rounding of a target entry of dZ is at most 2^-9 of it, independently per token
+    bound = GRAD_TOL * np.linalg.norm(soft_ref) + 1.1 * 2.0 ** -9 * np.linalg.norm(onehot_dw)
+    assert np.linalg.norm(soft_gpu - soft_ref) <= bound
+    if w_scale > 1.0:
+        assert np.linalg.norm(soft_ref) > 0.3 * np.linalg.norm(onehot_dw)
+        assert rel_l2(soft_gpu, soft_ref) < 2 * GRAD_TOL
+    # the same gradient from one chunk that holds every token: only the order of the fp32 sums differs
+    _, dx1, dw1 = run_fwd_bwd(spo, case, w_layout, chunk_tokens=0)
+    assert torch.equal(dx1, dx) and rel_l2(f64(dw1), got_dw) < 1e-4
+
+
 @pytest.mark.parametrize("keep,chunk", [(256, 256), (257, 256), (1, 0), (300, 512), (511, 256)])
 def test_backward_runs_over_active_tokens_only(spo, oracle, keep, chunk):
     # A sparse loss mask: the backward gathers the tokens that carry a gradient and works on
