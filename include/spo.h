@@ -213,7 +213,10 @@ typedef struct {
     const void *hidden;      /* [T, H] row-major                                     */
     const void *W;           /* H*V elements in w_layout                             */
     const void *logits;      /* [T, V] row-major, or NULL                            */
-    const int32_t *target;   /* [T] sampled token ids in [0, V)                      */
+    const int32_t *target;   /* [T] sampled token ids in [0, V); an id outside that
+                                range is not an error code: the token's logp is NaN
+                                (and with it the loss, if the token is unmasked) and
+                                its gradient row carries no one-hot term              */
     const float *old_logp;   /* [T] log-probs under the behaviour policy             */
     const uint8_t *mask;     /* [T] 0/1 loss mask, or NULL for all ones              */
     const float *adv_norm;   /* [B] normalised advantage per response                */
@@ -242,12 +245,15 @@ int spo_pg_loss_fwd(const spo_pg_desc *d, float *loss, float *logp, float *lse, 
  * accumulate_dW 1: add to the existing contents of d_W (mini-batch accumulation;
  *               needs d_W_dtype = SPO_FP32); 0: overwrite.
  * d_logits      [T, V] in desc dtype (logits-in form only).
- * chunk_tokens  tokens whose logit gradients are held in the workspace at once
- *               (0 picks the default, 131072).  The backward recomputes the logits
- *               tile by tile; a chunk's bf16 logit gradients (2 * V bytes per
- *               token) live in the workspace between the three contractions,
- *               never the full [T x V].  Fewer, larger chunks cost workspace and
- *               save passes over d_W, which is read and rewritten once per chunk.
+ * chunk_tokens  tokens whose logit gradients are held in the workspace at once,
+ *               rounded up to a multiple of 256.  The backward recomputes the logits
+ *               tile by tile; a chunk's bf16 logit gradients (2 * V bytes per token,
+ *               V rounded up to 256) live in the workspace between the three
+ *               contractions: at most chunk_tokens x V of them at a time, which is the
+ *               whole [T x V] array whenever T <= chunk_tokens.  0 lets the library
+ *               choose: as many tokens as keep that buffer within 8 GiB (24576 at
+ *               V = 151936, H = 4096).  Fewer, larger chunks cost workspace and save
+ *               passes over d_W, which is read and rewritten once per chunk.
  * Tokens whose gradient factor is zero (masked, on the clipped branch, or in a
  * response with zero advantage) are left out of the recompute and of both
  * contractions: the cost of the backward follows the number of remaining tokens,

@@ -110,6 +110,16 @@ def num_threads() -> int:
     return os.cpu_count() or 1
 
 
+def set_num_threads(n: int) -> None:
+    """Team size of the oracle's OpenMP loops from now on (the OpenMP runtime's own setter,
+    reached through the oracle library, which links it)."""
+    f = _load().omp_set_num_threads
+    f.restype = None
+    f.argtypes = [C.c_int]
+    f(int(n))
+    os.environ["OMP_NUM_THREADS"] = str(int(n))   # num_threads() reports this
+
+
 # --------------------------------------------------------------------- tracker
 def discount(kl, d_half, rho_min, rho_max) -> float:
     return float(_load().spo_oracle_discount(kl, d_half, rho_min, rho_max))

@@ -98,121 +98,120 @@ struct Tile {
         r = d & 3;
     }
 
+    // The two operand panels of one tile: A[m0.., :K] and B[n0.., :K], rows of ld bytes, M / N
+    // valid rows in all (rows of the tile beyond them are fetched from the last valid row; the
+    // caller masks them).  An operand may be stored in blocks of kBlockK contraction elements:
+    // element k of row m at base + (k / kBlockK) * blk + m * ld + (k % kBlockK) * 2 bytes
+    // (blk = 0: plain row-major).  With ld = 128 bytes a stage of a tile is then one contiguous
+    // 32 KiB piece instead of 256 lines a whole matrix row apart: the 256 rows stay within a few
+    // pages of the address translation and spread evenly over the memory channels.
+    struct Operands {
+        const char *A;
+        int64_t lda_bytes, m0, M;
+        const char *B;
+        int64_t ldb_bytes, n0, N;
+        int64_t a_blk, b_blk;
+    };
+
     // Global -> LDS transfers of one tile: addressing and issue.
     // Slot q = i*NT + tid of a tile <-> (row q/kChunks, position q%kChunks).
-    // An operand may be stored in blocks of kBlockK contraction elements: element k of row m at
-    // base + (k / kBlockK) * blk + m * ld + (k % kBlockK) * 2 bytes (blk = 0: plain row-major).
-    // With ld = 128 bytes a stage of a tile is then one contiguous 32 KiB piece instead of 256
-    // lines a whole matrix row apart: the 256 rows stay within a few pages of the address
-    // translation and spread evenly over the memory channels.
     struct Dma {
         const char *a_tile, *b_tile;     // first row of the A / B panel (wave-uniform)
         int64_t a_blk, b_blk;            // bytes from one block of kBlockK contraction elements to the next
         uint32_t oa[A_LOADS], ob[B_LOADS];  // this lane's byte offsets inside the panels
-        uint32_t lds_wave;               // LDS address of this wave's 1 KiB slice of stage 0
+        uint32_t lds_wave;               // LDS address of this wave's 1 KiB slice of buffer 0
 
-        __device__ __forceinline__ Dma(const char *A, int64_t lda_bytes, int64_t m0, int64_t M, const char *B,
-                                       int64_t ldb_bytes, int64_t n0, int64_t N, char *lds, int64_t a_blk_bytes,
-                                       int64_t b_blk_bytes)
-            : a_blk(a_blk_bytes ? a_blk_bytes : kBlockK * 2), b_blk(b_blk_bytes ? b_blk_bytes : kBlockK * 2) {
-            const int tid = threadIdx.x;
+        // the tile origins are the same for every lane; say so, the DMA wants them in SGPRs
+        __device__ static __forceinline__ const char *uniform(const char *p) {
+            const uint64_t u = reinterpret_cast<uint64_t>(p);
+            const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(u));
+            const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(u >> 32));
+            return reinterpret_cast<const char *>((static_cast<uint64_t>(hi) << 32) | lo);
+        }
+        __device__ static __forceinline__ uint32_t lds_address(const char *p) {
+            return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const char *)p));
+        }
+
+        __device__ __forceinline__ Dma(const Operands &t, char *lds)
+            : a_blk(t.a_blk ? t.a_blk : kBlockK * 2), b_blk(t.b_blk ? t.b_blk : kBlockK * 2) {
+            // The thread index goes through an empty asm so that the compiler cannot trace what is
+            // derived from it: hoisted out of a loop over tiles these few cheap values would sit
+            // in registers across the main loop, where every register counts.
+            int tid = threadIdx.x;
+            asm volatile("" : "+v"(tid));
             const int ld_row = tid / kChunks;
-            const int ld_chunk = (tid % kChunks) ^ swz(ld_row & 15);
-            // the tile origins are the same for every lane; say so, the DMA wants them in SGPRs
-            auto uniform = [](const char *p) {
-                const uint64_t u = reinterpret_cast<uint64_t>(p);
-                const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(u));
-                const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(u >> 32));
-                return reinterpret_cast<const char *>((static_cast<uint64_t>(hi) << 32) | lo);
-            };
-            a_tile = uniform(A + m0 * lda_bytes);
-            b_tile = uniform(B + n0 * ldb_bytes);
-            // 32-bit byte offsets from the tile's first row (a tile spans < 4 GiB)
+            const uint32_t ld_chunk16 = static_cast<uint32_t>(((tid % kChunks) ^ swz(ld_row & 15)) * 16);
+            a_tile = uniform(t.A + t.m0 * t.lda_bytes);
+            b_tile = uniform(t.B + t.n0 * t.ldb_bytes);
+            // 32-bit byte offsets from the tile's first row (a tile spans < 4 GiB); rows past the
+            // operand's last row are fetched from that last row
+            const uint32_t a_last = static_cast<uint32_t>(t.M - t.m0 >= BM ? BM - 1 : t.M - 1 - t.m0);
+            const uint32_t b_last = static_cast<uint32_t>(t.N - t.n0 >= BN ? BN - 1 : t.N - 1 - t.n0);
+            const uint32_t lda = static_cast<uint32_t>(t.lda_bytes), ldb = static_cast<uint32_t>(t.ldb_bytes);
 #pragma unroll
             for (int i = 0; i < A_LOADS; ++i) {
-                int64_t r = i * (NT / kChunks) + ld_row;
-                r = m0 + r < M ? r : M - 1 - m0;
-                oa[i] = static_cast<uint32_t>(r * lda_bytes + ld_chunk * 16);
+                const uint32_t r = static_cast<uint32_t>(i * (NT / kChunks) + ld_row);
+                oa[i] = (r < a_last ? r : a_last) * lda + ld_chunk16;
             }
 #pragma unroll
             for (int i = 0; i < B_LOADS; ++i) {
-                int64_t r = i * (NT / kChunks) + ld_row;
-                r = n0 + r < N ? r : N - 1 - n0;
-                ob[i] = static_cast<uint32_t>(r * ldb_bytes + ld_chunk * 16);
+                const uint32_t r = static_cast<uint32_t>(i * (NT / kChunks) + ld_row);
+                ob[i] = (r < b_last ? r : b_last) * ldb + ld_chunk16;
             }
-            lds_wave = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char *)lds)) +
-                       wave_id() * (kWave * 16);
+            lds_wave = lds_address(lds) + wave_id() * (kWave * 16);
         }
         // The DMA is issued from inline assembly.  Issued through the compiler it would
         // make every later LDS read wait for ALL outstanding DMA (the wait-count pass
         // cannot tell the stages apart); here every vmcnt wait for these loads is
-        // explicit instead.  M0 holds the LDS base of the 64 lanes x 16 bytes written.
+        // explicit instead.  M0 holds the LDS base of the 64 lanes x 16 bytes written.  (M0 cannot
+        // be named as a clobber: the compiler reserves the register and keeps no value of its
+        // own in it across an asm statement; these kernels use nothing else that goes through M0.)
         __device__ static __forceinline__ void dma(const char *base, uint32_t off, uint32_t lds_addr) {
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                          :
                          : "s"(lds_addr), "v"(off), "s"(base)
                          : "memory");
         }
-        // DMA instruction i (0 .. STAGE_LOADS-1) of this thread's share of stage kt
-        __device__ __forceinline__ void one(int kt, int i) const {
-            const uint32_t la = lds_wave + (kt % kStages) * STAGE_BYTES;
+        // DMA instruction i (0 .. STAGE_LOADS-1) of this thread's share of stage kt, into LDS buffer buf
+        __device__ __forceinline__ void one(int kt, int buf, int i) const {
+            const uint32_t la = lds_wave + buf * STAGE_BYTES;
             static_assert(kBlockK == kBK, "one block per stage");
             if (i < A_LOADS) dma(a_tile + kt * a_blk, oa[i], la + i * (NT * 16));
             else dma(b_tile + kt * b_blk, ob[i - A_LOADS], la + A_BYTES + (i - A_LOADS) * (NT * 16));
         }
-        __device__ __forceinline__ void stage(int kt) const {
+        __device__ __forceinline__ void stage(int kt, int buf) const {
 #pragma unroll
-            for (int i = 0; i < STAGE_LOADS; ++i) one(kt, i);
+            for (int i = 0; i < STAGE_LOADS; ++i) one(kt, buf, i);
         }
     };
 
-    // Starts the transfer of stage 0 of a tile while the caller still works on the
-    // previous tile's accumulators (its epilogue); the matching mainloop call passes
-    // stage0_issued = true.  All threads of the block must call this together.
-    __device__ static __forceinline__ void prefetch(const char *__restrict__ A, int64_t lda_bytes, int64_t m0, int64_t M,
-                                                    const char *__restrict__ B, int64_t ldb_bytes, int64_t n0, int64_t N,
-                                                    char *lds, int64_t a_blk = 0, int64_t b_blk = 0) {
-        const Dma d(A, lda_bytes, m0, M, B, ldb_bytes, n0, N, lds, a_blk, b_blk);
-        __syncthreads();  // every wave is done with the previous contents of lds
-        d.stage(0);
+    __device__ static __forceinline__ void fence_barrier() {
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
     }
 
-    // acc += A[m0.., :K] * B[n0.., :K]^T.  Rows beyond M / N are read from the last
-    // valid row (the caller masks them).  K = kBK * KT.  lds: LDS_BYTES bytes,
+    // acc += A[m0.., :K] * B[n0.., :K]^T for ONE tile, K = kBK * KT.  lds: LDS_BYTES bytes,
     // 16-byte aligned.  All threads of the block must call this together.
-    __device__ static __forceinline__ void mainloop(const char *__restrict__ A, int64_t lda_bytes, int64_t m0, int64_t M,
-                                                    const char *__restrict__ B, int64_t ldb_bytes, int64_t n0, int64_t N,
-                                                    int KT, char *lds, Acc &acc, bool stage0_issued = false,
-                                                    int64_t a_blk = 0, int64_t b_blk = 0) {
-        mainloop16(A, lda_bytes, m0, M, B, ldb_bytes, n0, N, KT, lds, acc, stage0_issued, a_blk, b_blk);
-    }
-
-    // Both wavefronts of a SIMD multiply at the same time and each hides its own fragment reads
-    // between its MFMAs (one read per two MFMAs, into a second register set for the next
-    // k-slice of 32); whenever one of them waits, at the barrier or for its operands, the
-    // other keeps the MFMA pipe fed.  One barrier per step, between the two k-slices: before it a wavefront has
-    // all its reads of stage s in registers and its share of stage s+1 landed; after it stage s+1
-    // may be read and the buffer of stage s is refilled with stage s+2 (one DMA instruction per
-    // four MFMAs).
-    __device__ static __forceinline__ void mainloop16(const char *__restrict__ A, int64_t lda_bytes, int64_t m0, int64_t M,
-                                                      const char *__restrict__ B, int64_t ldb_bytes, int64_t n0, int64_t N,
-                                                      int KT, char *lds, Acc &acc, bool stage0_issued, int64_t a_blk,
-                                                      int64_t b_blk) {
+    //
+    // Schedule of a step: both wavefronts of a SIMD multiply at the same time and each hides its
+    // own fragment reads between its MFMAs (one read per two MFMAs, into a second register set
+    // for the next k-slice of 32); whenever one of them waits, at the barrier or for its
+    // operands, the other keeps the MFMA pipe fed.  One barrier per step, between the two
+    // k-slices: before it a wavefront has all its reads of stage s in registers and its share of
+    // stage s+1 landed; after it stage s+1 may be read and the buffer of stage s is refilled with
+    // stage s+2 (one DMA instruction per four MFMAs).
+    __device__ static __forceinline__ void mainloop(const Operands &t, int KT, char *lds, Acc &acc) {
         static_assert(KK == 2 && kStages == 2, "two k-slices per stage, two stages");
         static_assert((FM + FN) * 2 <= FM * FN && STAGE_LOADS * 4 <= FM * FN, "reads and DMA fit between the MFMAs of a slice");
         const int lane = threadIdx.x & 63;
-        const Dma d(A, lda_bytes, m0, M, B, ldb_bytes, n0, N, lds, a_blk, b_blk);
+        const Dma d(t, lds);
         // lane reads row (l%16) of a 16-row block, chunk 4*kk + l/16
         const int fr_sw = swz(lane & 15);
         int fr_off[KK];
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) fr_off[kk] = (lane & 15) * kRowBytes + (((4 * kk + (lane >> 4)) ^ fr_sw) * 16);
         const int a_base = wave_m0() * kRowBytes, b_base = A_BYTES + wave_n0() * kRowBytes;
-        auto fence_barrier = [] {
-            __builtin_amdgcn_sched_barrier(0);
-            __builtin_amdgcn_s_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-        };
         bf16x8_t af[2][FM], bf[2][FN];
         // fragment r (0..FM+FN-1) of k-slice kk of stage kt into register set buf
         auto read_frag = [&](int kt, int kk, int buf, int r) {
@@ -220,12 +219,10 @@ struct Tile {
             if (r < FM) af[buf][r] = *reinterpret_cast<const bf16x8_t *>(st + a_base + r * (16 * kRowBytes) + fr_off[kk]);
             else bf[buf][r - FM] = *reinterpret_cast<const bf16x8_t *>(st + b_base + (r - FM) * (16 * kRowBytes) + fr_off[kk]);
         };
-        if (!stage0_issued) {
-            __syncthreads();  // every wave is done with the previous contents of lds
-            d.stage(0);
-        }
+        __syncthreads();  // every wave is done with the previous contents of lds
+        d.stage(0, 0);
         if (KT > 1) {
-            d.stage(1);
+            d.stage(1, 1);
             asm volatile("s_waitcnt vmcnt(%0)" ::"n"(STAGE_LOADS) : "memory");  // loads return in order: stage 0 has landed
         } else {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -260,7 +257,7 @@ struct Tile {
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 if (j % 4 == 1 && j / 4 < STAGE_LOADS) {
-                    if (FEED) d.one(kt + 2, j / 4);
+                    if (FEED) d.one(kt + 2, kt % kStages, j / 4);
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 acc[fm][fn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[1][fm], bf[1][fn], acc[fm][fn], 0, 0, 0);

@@ -58,7 +58,7 @@ token_loss_kernel(const float *__restrict__ part_max, const float *__restrict__ 
         if (!mask || mask[t]) {
             const float adv = adv_norm[response_of_token(cu, B, t)];
             const Surrogate r = surrogate(logp, old_logp[t], adv, eps_low, eps_high);
-            so = r.obj;
+            so = logp == logp ? r.obj : logp;  // a NaN log-prob (target id outside the vocabulary) reaches the loss
             cnt = 1.0;
             clp = r.active ? 0.0 : 1.0;
             sr = r.ratio;

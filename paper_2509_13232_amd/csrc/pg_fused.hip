@@ -28,9 +28,24 @@ namespace spo {
 typedef Tile<256, 256, 2, 4, 16> TL;
 constexpr int kSplitTerms = 6;    // cross products kept by the fp32 split
 constexpr int kSweepSplits = 16;  // vocabulary splits of the forward sweep on large problems (a multiple of 8)
-// tokens per backward chunk unless the caller says otherwise: 0.3 MB of bf16 logit gradients
-// per token at V = 151936, 40 GB per chunk; dW is read and rewritten once per chunk
-constexpr int64_t kDefaultChunk = 131072;
+// Default size of a backward chunk: as many tokens as keep the chunk's bf16 logit gradients
+// (2 * V bytes per token) within this budget, in whole rounds of dHidden tiles on the chip's
+// 256 compute units.  dW is read and rewritten once per chunk and every launch ends in a
+// partly filled round of tiles, so larger chunks (the caller's choice) are a little faster:
+// at H = 4096, V = 151936 the step takes about 1 % longer with 8 GiB than with 40 GB.
+constexpr int64_t kDzBudgetBytes = int64_t(8) << 30;
+constexpr int kChipCUs = 256;
+
+static int64_t gcd64(int64_t a, int64_t b) { return b ? gcd64(b, a % b) : a; }
+
+// tokens per chunk when the caller leaves the choice to the library (a multiple of the tile)
+static int64_t default_chunk_tokens(int64_t H, int64_t V_blk) {
+    const int64_t fit = kDzBudgetBytes / (2 * V_blk) / TL::BN * TL::BN;  // tokens within the budget
+    const int64_t nHt = (H + TL::BM - 1) / TL::BM;                        // dHidden tiles per token tile
+    const int64_t round = TL::BN * (kChipCUs / gcd64(kChipCUs, nHt));     // tokens per full round of tiles
+    if (fit >= round) return fit / round * round;
+    return fit > TL::BN ? fit : TL::BN;
+}
 
 // ----------------------------------------------------------------------------
 // operand preparation
@@ -164,16 +179,16 @@ __device__ __forceinline__ int64_t active_rows(const int32_t *n_act, int64_t row
 }
 
 // Rows [row_base, row_base + rows) of the compact order as contiguous copies: the hidden
-// states (Xc[r] = X[act_idx[row_base + r]]) and the per-token scalars the recompute needs.
-// Rows past the last active token are filled with zeros (g = 0, target = -1).
-// One workgroup per row.
+// states (Xc[r] = X[act_idx[row_base + r]]) and, packed into one 16-byte record per row, the
+// per-token scalars the recompute needs: tok[r] = (g, -lse * log2(e), target as bits, 0).
+// Rows past the last active token are filled with zeros and (0, -huge, -1, 0): scale zero and
+// an exponent that underflows, so that 0 * p stays 0.  One workgroup per row.
 template <typename T_>
 __global__ void __launch_bounds__(256)
 gather_chunk_kernel(const T_ *__restrict__ X, int64_t H, const int32_t *__restrict__ act_idx,
                     const int32_t *__restrict__ n_act, int64_t row_base, int64_t rows,
                     const int32_t *__restrict__ target, const float *__restrict__ lse, const float *__restrict__ g,
-                    T_ *__restrict__ Xc, int32_t *__restrict__ tgt_c, float *__restrict__ lse_c,
-                    float *__restrict__ g_c) {
+                    T_ *__restrict__ Xc, float4 *__restrict__ tok) {
     const int64_t r = blockIdx.x;
     const bool live = r < active_rows(n_act, row_base, rows);
     const int64_t src = live ? act_idx[row_base + r] : 0;
@@ -181,15 +196,58 @@ gather_chunk_kernel(const T_ *__restrict__ X, int64_t H, const int32_t *__restri
     const uint4 *in = reinterpret_cast<const uint4 *>(X + src * H);
     uint4 *out = reinterpret_cast<uint4 *>(Xc + r * H);
     for (int i = threadIdx.x; i < n16; i += 256) out[i] = live ? in[i] : make_uint4(0u, 0u, 0u, 0u);
-    if (threadIdx.x == 0) {
-        tgt_c[r] = live ? target[src] : -1;
-        lse_c[r] = live ? lse[src] : 0.0f;
-        g_c[r] = live ? g[src] : 0.0f;
-    }
+    if (threadIdx.x == 0)
+        tok[r] = live ? make_float4(g[src], -lse[src] * kLog2e, __int_as_float(target[src]), 0.0f)
+                      : make_float4(0.0f, kNegBig, __int_as_float(-1), 0.0f);
 }
 
 // ----------------------------------------------------------------------------
-// forward: vocabulary sweep with online log-sum-exp and target capture
+// forward: logit of the sampled token
+// ----------------------------------------------------------------------------
+// z_target[t] = h_t . W[target[t]] (W with one row per vocabulary entry), one wavefront per
+// token, products and sum in fp32.  The sweep below does not have to watch for this one
+// entry of every row.  An id outside [0, V) gives NaN (the token's log-prob, and with it the
+// loss, then say so instead of carrying an arbitrary number).
+__device__ __forceinline__ float dot8(const uint4 a, const uint4 b) {
+    const uint32_t x[4] = {a.x, a.y, a.z, a.w}, y[4] = {b.x, b.y, b.z, b.w};
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        s = fmaf(__uint_as_float(x[i] << 16), __uint_as_float(y[i] << 16), s);
+        s = fmaf(__uint_as_float(x[i] & 0xffff0000u), __uint_as_float(y[i] & 0xffff0000u), s);
+    }
+    return s;
+}
+
+template <typename T_>
+__global__ void __launch_bounds__(256)
+target_logit_kernel(const T_ *__restrict__ X, const T_ *__restrict__ Wvh, int64_t H, int64_t V, int64_t T,
+                    const int32_t *__restrict__ target, float *__restrict__ z_target) {
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (t >= T) return;
+    const int64_t y = target[t];
+    if (y < 0 || y >= V) {
+        if (lane == 0) z_target[t] = __builtin_nanf("");
+        return;
+    }
+    float s = 0.0f;
+    if constexpr (sizeof(T_) == 2) {
+        const uint4 *x = reinterpret_cast<const uint4 *>(X + t * H), *w = reinterpret_cast<const uint4 *>(Wvh + y * H);
+        for (int i = lane; i < H / 8; i += kWave) s += dot8(x[i], w[i]);  // H is a multiple of 64
+    } else {
+        const float4 *x = reinterpret_cast<const float4 *>(X + t * H), *w = reinterpret_cast<const float4 *>(Wvh + y * H);
+        for (int i = lane; i < H / 4; i += kWave) {
+            const float4 a = x[i], b = w[i];
+            s = fmaf(a.x, b.x, s); s = fmaf(a.y, b.y, s); s = fmaf(a.z, b.z, s); s = fmaf(a.w, b.w, s);
+        }
+    }
+    s = wave_sum(s);
+    if (lane == 0) z_target[t] = s;
+}
+
+// ----------------------------------------------------------------------------
+// forward: vocabulary sweep with online log-sum-exp
 // ----------------------------------------------------------------------------
 // Tile rows (m) are vocabulary entries, tile columns (n) are tokens, so that each
 // lane owns FN tokens and reduces over the vocabulary inside its own registers.
@@ -199,11 +257,12 @@ gather_chunk_kernel(const T_ *__restrict__ X, int64_t H, const int32_t *__restri
 // of them, each head tile 4), and the patches of one group of 4 token tiles follow
 // one another.  More than 8 splits shorten a workgroup's sweep: workgroups that share
 // lines then have less time to drift apart before new ones start in step.
+constexpr int kSweepLds = TL::LDS_BYTES + TL::NT * 32;  // operand stages + the per-thread running state
+
 __global__ void __launch_bounds__(TL::NT)
 fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const char *__restrict__ X,
-                 int64_t ldx_bytes, int64_t T, int KT, const int32_t *__restrict__ target, int nsplit,
-                 int64_t nTt, int64_t nVt, int64_t T_pad, float *__restrict__ part_max,
-                 float *__restrict__ part_sum, float *__restrict__ z_target) {
+                 int64_t ldx_bytes, int64_t T, int KT, int nsplit, int64_t nTt, int64_t nVt, int64_t T_pad,
+                 float *__restrict__ part_max, float *__restrict__ part_sum) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int64_t bid = blockIdx.x, xcd = bid & 7, q = bid >> 3;
     int split;
@@ -222,22 +281,19 @@ fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const
     const int64_t vt0 = split * nVt / nsplit, vt1 = (split + 1) * nVt / nsplit;
     const int lane = threadIdx.x & 63;
 
-    float m_run[TL::FN], s_run[TL::FN];
-    int32_t tgt[TL::FN];
-#pragma unroll
-    for (int fn = 0; fn < TL::FN; ++fn) {
-        m_run[fn] = kNegBig;
-        s_run[fn] = 0.0f;
-        const int64_t t = n0 + TL::acc_col(fn);
-        tgt[fn] = t < T ? target[t] : -1;
-    }
-    for (int64_t vt = vt0; vt < vt1; ++vt) {
-        const int64_t m0 = vt * TL::BM;
-        TL::Acc acc;
-        TL::zero(acc);
-        TL::mainloop(W, ldw_bytes, m0, V, X, ldx_bytes, n0, T, KT, lds, acc, vt > vt0);
-        // the first stage of the next vocabulary tile travels while this one is reduced
-        if (vt + 1 < vt1) TL::prefetch(W, ldw_bytes, m0 + TL::BM, V, X, ldx_bytes, n0, T, lds);
+    // Running (maximum, sum of exponentials) of this lane's FN tokens.  Between tiles they wait in
+    // the LDS the operand stages leave free (a slot per thread): the main loop needs every register.
+    static_assert(TL::FN == 4, "one 16-byte slot each for the maxima and the sums");
+    auto state = [&] {
+        int tid = threadIdx.x;
+        asm volatile("" : "+v"(tid));  // not to be traced: the address is formed anew at every use
+        return reinterpret_cast<float4 *>(lds + TL::LDS_BYTES) + 2 * tid;
+    };
+    state()[0] = make_float4(kNegBig, kNegBig, kNegBig, kNegBig);
+    state()[1] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    // online log-sum-exp over the rows of one finished tile: three operations per logit
+    // (multiply-add into the exponent, exponential, add) plus its share of the maximum
+    auto reduce = [&](TL::Acc &acc, int64_t m0) {
         if (m0 + TL::BM > V) {  // ragged last tile: rows past the vocabulary do not count
 #pragma unroll
             for (int fm = 0; fm < TL::FM; ++fm)
@@ -245,47 +301,46 @@ fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const
                 for (int r = 0; r < TL::ACC_R; ++r)
                     if (m0 + TL::acc_row(fm, r) >= V)
 #pragma unroll
-                        for (int fn = 0; fn < TL::FN; ++fn) acc[fm][fn][r] = kNegBig;
+                        for (int fn = 0; fn < TL::FN; ++fn) acc[fm][fn][r] = -INFINITY;
         }
+        float4 *st = state();
+        const float4 m4 = st[0], s4 = st[1];
+        float m_run[TL::FN] = {m4.x, m4.y, m4.z, m4.w}, s_run[TL::FN] = {s4.x, s4.y, s4.z, s4.w};
 #pragma unroll
         for (int fn = 0; fn < TL::FN; ++fn) {
-            float mx = kNegBig;
+            float mx = -INFINITY;
 #pragma unroll
             for (int fm = 0; fm < TL::FM; ++fm)
 #pragma unroll
                 for (int r = 0; r < TL::ACC_R; ++r) mx = fmaxf(mx, acc[fm][fn][r]);
+            // the running maximum starts at a finite sentinel, so nm is finite even when every
+            // row of the tile is masked (their logits are -inf and add exact zeros)
             const float nm = fmaxf(m_run[fn], mx);
+            const float c = -nm * kLog2e;
             float s = 0.0f;
-            // subtract first: with every row masked nm is the sentinel itself and the
-            // difference must be an exact zero, which a fused multiply-add of two huge
-            // rounded products would not give
 #pragma unroll
             for (int fm = 0; fm < TL::FM; ++fm)
 #pragma unroll
-                for (int r = 0; r < TL::ACC_R; ++r) s += __builtin_amdgcn_exp2f((acc[fm][fn][r] - nm) * kLog2e);
+                for (int r = 0; r < TL::ACC_R; ++r) s += __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r], kLog2e, c));
             s_run[fn] = s_run[fn] * __builtin_amdgcn_exp2f((m_run[fn] - nm) * kLog2e) + s;
             m_run[fn] = nm;
-            // the sampled token's logit, if its vocabulary row is one of mine
-            const int d = tgt[fn] - static_cast<int>(m0 + TL::wave_m0());
-            if (static_cast<unsigned>(d) < static_cast<unsigned>(TL::WM)) {
-                int fq, rq, gq;
-                TL::locate(d, fq, rq, gq);
-                if (gq == TL::lane_group()) {
-                    float z = 0.0f;
-#pragma unroll
-                    for (int fm = 0; fm < TL::FM; ++fm)
-#pragma unroll
-                        for (int r = 0; r < TL::ACC_R; ++r)
-                            if (fm == fq && r == rq) z = acc[fm][fn][r];
-                    z_target[n0 + TL::acc_col(fn)] = z;
-                }
-            }
         }
+        st[0] = make_float4(m_run[0], m_run[1], m_run[2], m_run[3]);
+        st[1] = make_float4(s_run[0], s_run[1], s_run[2], s_run[3]);
+    };
+    auto tile_ops = [&](int64_t vt) { return typename TL::Operands{W, ldw_bytes, vt * TL::BM, V, X, ldx_bytes, n0, T, 0, 0}; };
+    for (int64_t vt = vt0; vt < vt1; ++vt) {
+        TL::Acc acc;
+        TL::zero(acc);
+        TL::mainloop(tile_ops(vt), KT, lds, acc);
+        reduce(acc, vt * TL::BM);
     }
     // merge the lane groups that hold different rows of the same token, then the WGM
     // wavefronts that share a token column
     float *red_m = reinterpret_cast<float *>(lds);
     float *red_s = red_m + TL::WGM * TL::BN;
+    const float4 m4 = state()[0], s4 = state()[1];
+    const float m_run[TL::FN] = {m4.x, m4.y, m4.z, m4.w}, s_run[TL::FN] = {s4.x, s4.y, s4.z, s4.w};
     __syncthreads();  // operand stages are no longer read
 #pragma unroll
     for (int fn = 0; fn < TL::FN; ++fn) {
@@ -318,94 +373,131 @@ fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const
 }
 
 // ----------------------------------------------------------------------------
-// backward, step 1: recompute a logits tile and emit its bf16 gradient
+// backward, step 1: recompute the logits tile by tile and emit their bf16 gradient
 // ----------------------------------------------------------------------------
 // dz[t][v] = g[t] * ([v == target[t]] - exp(z[t][v] - lse[t])), written once, in blocks
 // of kBlockK = 64 vocabulary entries: dz[t][v] at dZ + (v / 64) * dz_blk + t * 64 + v % 64
-// (dz_blk elements per block = rows of the chunk * 64).  A tile of this kernel is four
-// contiguous 32 KiB pieces.  dHidden reads the blocks as a k-blocked operand (contraction
-// over v: one block per k-step), dW reads four neighbouring blocks as a matrix with the
-// tokens as rows (contraction over t).  Entries with v >= V and tokens past T_valid are
-// written as zeros.  Token tiles that start at or after the
-// number of active rows of this chunk (device value n_act[0] - row_base) are
+// (dz_blk elements per block = rows of the chunk * 64).  dHidden reads the blocks as a
+// k-blocked operand (contraction over v: one block per k-step), dW reads four neighbouring
+// blocks as a matrix with the tokens as rows (contraction over t).  Entries with v >= V and
+// tokens past the active rows of their tile are written as zeros.  Token tiles that start at
+// or after the number of active rows of this chunk (device value n_act[0] - row_base) are
 // skipped altogether.
+//
+// Persistent workgroups, one per compute unit: workgroup (XCD x, slot j) computes tile j of
+// every patch of 4 x 8 tiles that TileOrder gives XCD x, one after the other.  The gradients
+// go from the accumulators to memory without a detour through LDS.
+
+// 4 x 4 transpose of 32-bit values across the four groups of 16 lanes of a wavefront: on
+// return register q of lane group g holds what register g of lane group q held.
+// v_permlane32_swap(a, b) exchanges the upper 32 lanes of a with the lower 32 lanes of b,
+// v_permlane16_swap(a, b) the odd groups of 16 lanes of a with the even groups of b.
+__device__ __forceinline__ void transpose_lane_groups(uint32_t &r0, uint32_t &r1, uint32_t &r2, uint32_t &r3) {
+    typedef unsigned v2u __attribute__((ext_vector_type(2)));
+    v2u t = __builtin_amdgcn_permlane32_swap(r0, r2, false, false);
+    r0 = t.x; r2 = t.y;
+    t = __builtin_amdgcn_permlane32_swap(r1, r3, false, false);
+    r1 = t.x; r3 = t.y;
+    t = __builtin_amdgcn_permlane16_swap(r0, r1, false, false);
+    r0 = t.x; r1 = t.y;
+    t = __builtin_amdgcn_permlane16_swap(r2, r3, false, false);
+    r2 = t.x; r3 = t.y;
+}
+
 __global__ void __launch_bounds__(TL::NT)
 recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V,
                     const char *__restrict__ X, int64_t ldx_bytes, int64_t T_valid, int KT,
-                    const int32_t *__restrict__ target, const float *__restrict__ lse,
-                    const float *__restrict__ g, int64_t nVt, int64_t nTt, bf16_t *__restrict__ dZ,
+                    const float4 *__restrict__ tok, int64_t nVt, int64_t nTt, bf16_t *__restrict__ dZ,
                     int64_t dz_blk, const int32_t *__restrict__ n_act, int64_t row_base) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    int64_t tm, tn;
-    if (!TileOrder(nVt, nTt).tile(blockIdx.x, tm, tn)) return;
-    const int64_t m0 = tm * TL::BM, n0 = tn * TL::BN;
-    if (n0 >= active_rows(n_act, row_base, T_valid)) return;  // token tiles past the last active token
-    TL::Acc acc;
-    TL::zero(acc);
-    TL::mainloop(W, ldw_bytes, m0, V, X, ldx_bytes, n0, T_valid, KT, lds, acc);
-    if (m0 + TL::BM > V) {  // ragged last tile: rows past the vocabulary get probability zero
-#pragma unroll
-        for (int fm = 0; fm < TL::FM; ++fm)
-#pragma unroll
-            for (int r = 0; r < TL::ACC_R; ++r)
-                if (m0 + TL::acc_row(fm, r) >= V)
-#pragma unroll
-                    for (int fn = 0; fn < TL::FN; ++fn) acc[fm][fn][r] = kNegBig;
-    }
-    // The tile goes out through LDS (the operand stages are free now).  A lane holds runs of
-    // four consecutive vocabulary entries of ONE token, so stored directly a wavefront would
-    // scatter 64 pieces of 8 bytes over many rows per instruction; from LDS every store
-    // instruction writes two full rows of 512 bytes.
-    //   256 token rows x 512 B, 16-byte chunk c of row t at position c ^ (t % 32)
-    static_assert(TL::LDS_BYTES >= TL::BN * 512 && TL::BM * 2 == 512, "a tile of bf16 gradients fits the operand stages");
-    const int lane = threadIdx.x & 63;
-#pragma unroll
-    for (int fn = 0; fn < TL::FN; ++fn) {
-        const int tl = TL::acc_col(fn);
-        const int64_t t = n0 + tl;
-        const bool tok_ok = t < T_valid;
-        const float gt = tok_ok ? g[t] : 0.0f;
-        const float ngt = -gt;
-        // padded tokens: scale zero and an exponent that underflows, so that 0 * p stays 0
-        const float nl = tok_ok ? -lse[t] * kLog2e : kNegBig;
-        // where the target's vocabulary row sits among this wave's rows, if it does
-        const int dy = (tok_ok ? target[t] : -1) - static_cast<int>(m0 + TL::wave_m0());
-        int fq = 0, rq = 0, gq = 0;
-        const bool in_wave = static_cast<unsigned>(dy) < static_cast<unsigned>(TL::WM);
-        if (in_wave) TL::locate(dy, fq, rq, gq);
-        const bool mine = in_wave && gq == TL::lane_group();
-#pragma unroll
-        for (int fm = 0; fm < TL::FM; ++fm) {
-#pragma unroll
-            for (int r4 = 0; r4 < TL::RUNS; ++r4) {
-                const int vl = TL::acc_row(fm, r4 * 4);  // first of my 4 consecutive rows, tile-local
-                float dz[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    dz[i] = ngt * __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r4 * 4 + i], kLog2e, nl));
-                if (mine && fm == fq && (rq >> 2) == r4) {  // the one-hot term
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if ((rq & 3) == i) dz[i] += gt;
-                }
-                uint2 pk;  // bf16 gradients: .x = rows +0,+1, .y = rows +2,+3 of the run, my token
-                pk.x = pack_bf16x2_rn(dz[0], dz[1]);
-                pk.y = pack_bf16x2_rn(dz[2], dz[3]);
-                *reinterpret_cast<uint2 *>(lds + tl * 512 + (((vl >> 3) ^ (tl & 31)) << 4) + (vl & 4) * 2) = pk;
+    static_assert(TL::BM % kBlockK == 0 && kBlockK == 4 * TL::MI && TL::FM % 4 == 0,
+                  "a block of dZ is four MFMA blocks of vocabulary rows");
+    const TileOrder ord(nVt, nTt);
+    const int act = static_cast<int>(active_rows(n_act, row_base, T_valid));
+    const int xcd = blockIdx.x & 7;
+    const int slot = blockIdx.x >> 3, nslot = gridDim.x >> 3, n_items = static_cast<int>(ord.blocks() >> 3);
+    // item i of this XCD is what TileOrder calls workgroup i * 8 + xcd; first valid item at or after `item`
+    auto advance = [&](int item, int &tm, int &tn) {
+        for (; item < n_items; item += nslot) {
+            int64_t a, b;
+            if (ord.tile(static_cast<int64_t>(item) * 8 + xcd, a, b) && b * TL::BN < act) {
+                tm = static_cast<int>(a);
+                tn = static_cast<int>(b);
+                break;
             }
         }
-    }
-    __syncthreads();
-    // every wavefront writes 32 token rows, two rows (2 x 512 contiguous bytes) per store
-    const int ci = lane & 31;  // 16-byte chunk of a row that this lane writes out
-    static_assert(TL::BM % kBlockK == 0, "a vocabulary tile is a whole number of blocks of dZ");
-    constexpr int cpb = kBlockK / 8;  // 16-byte chunks per block row
-    bf16_t *piece = dZ + (tm * (TL::BM / kBlockK) + ci / cpb) * dz_blk + n0 * kBlockK + (ci % cpb) * 8;
+        return item;
+    };
+    int tm = 0, tn = 0;
+    int item = advance(slot, tm, tn);
+    auto tile_ops = [&](int tile_m, int tile_n) {
+        return typename TL::Operands{W, ldw_bytes, static_cast<int64_t>(tile_m) * TL::BM, V, X, ldx_bytes,
+                                     static_cast<int64_t>(tile_n) * TL::BN, T_valid, 0, 0};
+    };
+    // gradients of one finished tile
+    auto emit = [&](TL::Acc &acc, int tile_m, int tile_n) {
+        const int m0 = tile_m * TL::BM, n0 = tile_n * TL::BN;
+        if (m0 + TL::BM > V) {  // ragged last tile: rows past the vocabulary get probability zero
 #pragma unroll
-    for (int i = 0; i < TL::BN / TL::NWAVE / 2; ++i) {
-        const int tl = TL::wave_id() * (TL::BN / TL::NWAVE) + 2 * i + (lane >> 5);
-        const uint4 v = *reinterpret_cast<const uint4 *>(lds + tl * 512 + ((ci ^ (tl & 31)) << 4));
-        *reinterpret_cast<uint4 *>(piece + tl * kBlockK) = v;
+            for (int fm = 0; fm < TL::FM; ++fm)
+#pragma unroll
+                for (int r = 0; r < TL::ACC_R; ++r)
+                    if (m0 + TL::acc_row(fm, r) >= V)
+#pragma unroll
+                        for (int fn = 0; fn < TL::FN; ++fn) acc[fm][fn][r] = kNegBig;
+        }
+        // A lane holds runs of four consecutive vocabulary entries (8 bytes of bf16) of ONE token,
+        // at offset 32 * (fm % 4) + 8 * group inside that token's 128-byte row of a block of dZ.
+        // Transposed across the four lane groups, the lane of group q holds 32 contiguous bytes
+        // (the runs with fm % 4 == q of all four groups): two 16-byte stores per block.
+        // (Everything that depends on the lane is derived here from a value the compiler cannot
+        // trace, so that none of it is kept in registers across the main loop.)
+        int lane = threadIdx.x & 63;
+        asm volatile("" : "+v"(lane));
+        const int grp = lane >> 4, col = lane & 15;
+        const int wave_blk = tile_m * (TL::BM / kBlockK) + TL::wave_m0() / kBlockK;
+        const float4 *tok_w = tok + static_cast<int64_t>(n0) + TL::wave_n0();  // records of this wavefront's 64 tokens
+#pragma unroll
+        for (int fn = 0; fn < TL::FN; ++fn) {
+            const float4 tk = tok_w[fn * TL::MI + col];
+            const float gt = tk.x, ngt = -gt, nl = tk.y;
+            // where the target's vocabulary row sits among this wave's rows, if it does
+            const int dy = __float_as_int(tk.z) - (m0 + TL::wave_m0());
+            int fq = 0, rq = 0, gq = 0;
+            const bool in_wave = static_cast<unsigned>(dy) < static_cast<unsigned>(TL::WM);
+            if (in_wave) TL::locate(dy, fq, rq, gq);
+            const bool mine = in_wave && gq == grp;
+            bf16_t *row = dZ + static_cast<int64_t>(n0 + TL::wave_n0() + fn * TL::MI + col) * kBlockK + grp * 16;
+#pragma unroll
+            for (int b = 0; b < TL::FM / 4; ++b) {
+                uint32_t lo[4], hi[4];  // bf16 pairs: lo = rows +0,+1, hi = rows +2,+3 of the run of block 4b+q
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int fm = 4 * b + q;
+                    float dz[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) dz[i] = ngt * __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][i], kLog2e, nl));
+                    if (mine && fm == fq) {  // the one-hot term
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (rq == i) dz[i] += gt;
+                    }
+                    lo[q] = pack_bf16x2_rn(dz[0], dz[1]);
+                    hi[q] = pack_bf16x2_rn(dz[2], dz[3]);
+                }
+                transpose_lane_groups(lo[0], lo[1], lo[2], lo[3]);
+                transpose_lane_groups(hi[0], hi[1], hi[2], hi[3]);
+                uint4 *out = reinterpret_cast<uint4 *>(row + (wave_blk + b) * dz_blk);
+                out[0] = make_uint4(lo[0], hi[0], lo[1], hi[1]);
+                out[1] = make_uint4(lo[2], hi[2], lo[3], hi[3]);
+            }
+        }
+    };
+    for (; item < n_items; item = advance(item + nslot, tm, tn)) {
+        TL::Acc acc;
+        TL::zero(acc);
+        TL::mainloop(tile_ops(tm, tn), KT, lds, acc);
+        emit(acc, tm, tn);
     }
 }
 
@@ -426,17 +518,33 @@ recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V,
 // the contraction index, rounded up to whole tiles of tokens (dW).
 constexpr int kLimitRows = 1, kLimitK = 2;
 
+// With nsplit > 1 (plain form only) the contraction is cut into nsplit equal runs of k-steps;
+// workgroup (tile, part) writes its fp32 partial tile to partials[part][m][n] (leading
+// dimension N) and reduce_split_kernel adds the parts in a fixed order: shapes with fewer
+// tiles than the chip has compute units still fill it, and the result does not depend on timing.
+//
+// Epilogue: the accumulators go out through LDS (the operand stages are free by then), half a
+// tile at a time: a lane holds four consecutive ROWS of one column, so stored directly a
+// wavefront would scatter 64-byte pieces over many rows per instruction; from LDS every
+// wavefront writes (or reads, adds and rewrites) whole rows of 256 values, 16 bytes per lane.
+// LDS layout of a half tile: 128 rows x 1024 bytes, the 64-byte piece c of row r at position
+// c ^ ((r / 4) % 4): the four lane groups, whose rows lie 4 apart, hit different banks.
 template <bool KMajor>
 __global__ void __launch_bounds__(TL::NT)
 gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, const char *__restrict__ B,
                   int64_t ldb_bytes, int64_t N, int KT, void *__restrict__ out, int64_t ldo, int out_dtype,
                   int accumulate, const int32_t *__restrict__ n_act, int64_t row_base, int limit,
-                  const int32_t *__restrict__ row_map, int64_t a_blk, int64_t b_blk) {
+                  const int32_t *__restrict__ row_map, int64_t a_blk, int64_t b_blk, int nsplit,
+                  float *__restrict__ partials) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     constexpr int bpt = TL::BM / kBlockK;  // blocks per tile edge
     static_assert(TL::BM % kBlockK == 0 && TL::BN == TL::BM, "a tile of a blocked operand is a whole number of blocks");
+    static_assert(TL::WGM == 2 && TL::BN * 4 * (TL::BM / 2) <= TL::LDS_BYTES, "half a tile of fp32 fits the operand stages");
+    const TileOrder ord(ceil_div(M, TL::BM), ceil_div(N, TL::BN));
+    const int64_t per_part = ord.blocks();
+    const int part = static_cast<int>(blockIdx.x / per_part);
     int64_t tm, tn;
-    if (!TileOrder(ceil_div(M, TL::BM), ceil_div(N, TL::BN)).tile(blockIdx.x, tm, tn)) return;
+    if (!ord.tile(blockIdx.x % per_part, tm, tn)) return;
     const int64_t m0 = tm * TL::BM, n0 = tn * TL::BN;
     int64_t m_end = M;
     if (n_act && limit == kLimitRows) {
@@ -448,6 +556,12 @@ gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, cons
         KT = __builtin_amdgcn_readfirstlane(static_cast<int>(ceil_div(k_rows, TL::BN) * (TL::BN / kBK)));
         if (KT == 0 && accumulate) return;  // nothing to add
     }
+    int kt0 = 0;
+    if (nsplit > 1) {  // this part's run of k-steps
+        const int per = (KT + nsplit - 1) / nsplit;
+        kt0 = part * per;
+        KT = KT - kt0 < per ? KT - kt0 : per;
+    }
     TL::Acc acc;
     TL::zero(acc);
     if (KT > 0) {
@@ -457,27 +571,102 @@ gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, cons
                                 b_blk ? B + tn * bpt * b_blk : B, ldb_bytes, b_blk ? 0 : n0, b_blk ? TL::BN : Nr, KT, lds,
                                 acc, a_blk, b_blk);
         } else {
-            TL::mainloop(A, lda_bytes, m0, M, B, ldb_bytes, n0, N, KT, lds, acc, false, a_blk, b_blk);
+            // k-step kt of an operand starts blk bytes (blocked) or one stage of 128 bytes (row-major) further on
+            const int64_t sa = a_blk ? a_blk : kBK * 2, sb = b_blk ? b_blk : kBK * 2;
+            TL::mainloop(typename TL::Operands{A + kt0 * sa, lda_bytes, m0, M, B + kt0 * sb, ldb_bytes, n0, N, a_blk, b_blk},
+                         KT, lds, acc);
         }
     }
+    if (nsplit > 1) {  // partial tiles: plain fp32 rows of N values, no row map
+        out = partials + static_cast<int64_t>(part) * M * N;
+        ldo = N;
+        out_dtype = SPO_FP32;
+        accumulate = 0;
+        row_map = nullptr;
+    }
+    int lane = threadIdx.x & 63;
+    asm volatile("" : "+v"(lane));  // not to be traced: nothing derived from it is to live through the main loop
+    const int grp = lane >> 4, col = lane & 15;
+    // whole groups of four columns can move as 16 (fp32) or 8 (bf16) bytes when the rows allow it
+    const bool vec = ldo % 4 == 0 && N % 4 == 0 && reinterpret_cast<uintptr_t>(out) % 16 == 0;
+    constexpr int HALF = TL::BM / 2, ROWS = HALF / TL::NWAVE;
+    __syncthreads();  // the operand stages are no longer read
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+        if (TL::wave_m0() == half * HALF) {
 #pragma unroll
-    for (int fn = 0; fn < TL::FN; ++fn) {
-        const int64_t n = n0 + TL::acc_col(fn);
-        if (n >= N) continue;
+            for (int fm = 0; fm < TL::FM; ++fm)
 #pragma unroll
-        for (int fm = 0; fm < TL::FM; ++fm)
+                for (int fn = 0; fn < TL::FN; ++fn)
 #pragma unroll
-            for (int r = 0; r < TL::ACC_R; ++r) {
-                int64_t m = m0 + TL::acc_row(fm, r);
-                if (m >= m_end) continue;
-                if (row_map) m = row_map[m];
-                if (out_dtype == SPO_FP32) {
-                    float *o = static_cast<float *>(out) + m * ldo + n;
-                    *o = accumulate ? *o + acc[fm][fn][r] : acc[fm][fn][r];
+                    for (int r = 0; r < TL::ACC_R; ++r) {
+                        const int row = fm * TL::MI + 4 * grp + r;                  // (row / 4) % 4 == grp
+                        const int piece = (TL::wave_n0() / TL::MI + fn) ^ grp;     // 64-byte piece of the row
+                        *reinterpret_cast<float *>(lds + row * (TL::BN * 4) + piece * 64 + col * 4) = acc[fm][fn][r];
+                    }
+        }
+        __syncthreads();
+        const int64_t n = n0 + 4 * lane;  // this lane's four columns
+#pragma unroll 4
+        for (int i = 0; i < ROWS; ++i) {
+            const int row = TL::wave_id() * ROWS + i;
+            int64_t m = m0 + half * HALF + row;
+            if (m >= m_end) break;  // rows are in order: nothing further down either
+            if (row_map) m = row_map[m];
+            const float4 v = *reinterpret_cast<const float4 *>(lds + row * (TL::BN * 4) + (((lane >> 2) ^ ((row >> 2) & 3)) << 6) +
+                                                               (lane & 3) * 16);
+            if (n >= N) continue;
+            if (out_dtype == SPO_FP32) {
+                float *o = static_cast<float *>(out) + m * ldo + n;
+                if (vec) {
+                    float4 w = v;
+                    if (accumulate) {
+                        const float4 old = *reinterpret_cast<const float4 *>(o);
+                        w = make_float4(old.x + v.x, old.y + v.y, old.z + v.z, old.w + v.w);
+                    }
+                    *reinterpret_cast<float4 *>(o) = w;
                 } else {
-                    static_cast<bf16_t *>(out)[m * ldo + n] = f32_to_bf16(acc[fm][fn][r]);
+                    const float e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (n + j < N) o[j] = accumulate ? o[j] + e[j] : e[j];
+                }
+            } else {
+                bf16_t *o = static_cast<bf16_t *>(out) + m * ldo + n;
+                if (vec) {
+                    *reinterpret_cast<uint2 *>(o) = make_uint2(pack_bf16x2_rn(v.x, v.y), pack_bf16x2_rn(v.z, v.w));
+                } else {
+                    const float e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (n + j < N) o[j] = f32_to_bf16(e[j]);
                 }
             }
+        }
+        __syncthreads();  // the half tile has been read: its space may be written again
+    }
+}
+
+// out[row_map[m]][n] = sum over the parts (in order) of partials[part][m][n] for m below the
+// number of active rows; four values per thread (N is a multiple of 4 here).
+__global__ void __launch_bounds__(256)
+reduce_split_kernel(const float *__restrict__ partials, int nsplit, int64_t M, int64_t N,
+                    const int32_t *__restrict__ n_act, int64_t row_base, const int32_t *__restrict__ row_map,
+                    void *__restrict__ out, int64_t ldo, int out_dtype) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    const int64_t per_row = N / 4, m = i / per_row, n = (i % per_row) * 4;
+    if (m >= active_rows(n_act, row_base, M)) return;
+    float4 s = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    for (int p = 0; p < nsplit; ++p) {
+        const float4 v = *reinterpret_cast<const float4 *>(partials + (static_cast<int64_t>(p) * M + m) * N + n);
+        s = make_float4(s.x + v.x, s.y + v.y, s.z + v.z, s.w + v.w);
+    }
+    const int64_t mo = row_map[m];
+    if (out_dtype == SPO_FP32) {
+        *reinterpret_cast<float4 *>(static_cast<float *>(out) + mo * ldo + n) = s;
+    } else {
+        *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(out) + mo * ldo + n) =
+            make_uint2(pack_bf16x2_rn(s.x, s.y), pack_bf16x2_rn(s.z, s.w));
     }
 }
 
@@ -490,7 +679,7 @@ gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, cons
 static int set_lds_limit() {
     hipError_t e = hipSuccess;
     e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_sweep_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kSweepLds);
     e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(recompute_dz_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
     e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_store_kernel<false>),
@@ -585,9 +774,19 @@ int fused_fwd(const spo_pg_desc *d, float *loss, float *logp, float *lse, float 
         const int64_t per_xcd = p.nsplit % 8 == 0 ? round_up(ceil_div(p.nTt, 8), 4) : ceil_div(p.nTt, 8);
         const int64_t blocks = per_xcd * 8 * p.nsplit;
         ScopedKernelTimer timer(kTimeFwdSweep, s);
-        fwd_sweep_kernel<<<static_cast<unsigned>(blocks), TL::NT, TL::LDS_BYTES, s>>>(
-            W, p.Kc * 2, d->V, X, p.Kc * 2, d->T, static_cast<int>(p.Kc / kBK), d->target, p.nsplit, p.nTt, p.nVt,
-            p.T_pad, p.part_max, p.part_sum, p.z_target);
+        fwd_sweep_kernel<<<static_cast<unsigned>(blocks), TL::NT, kSweepLds, s>>>(
+            W, p.Kc * 2, d->V, X, p.Kc * 2, d->T, static_cast<int>(p.Kc / kBK), p.nsplit, p.nTt, p.nVt, p.T_pad,
+            p.part_max, p.part_sum);
+    }
+    if (d->T > 0) {
+        if (d->dtype == SPO_FP32)
+            target_logit_kernel<float><<<grid1(d->T, 4), 256, 0, s>>>(
+                static_cast<const float *>(d->hidden), d->w_layout == SPO_W_HV ? p.W32 : static_cast<const float *>(d->W),
+                d->H, d->V, d->T, d->target, p.z_target);
+        else
+            target_logit_kernel<bf16_t><<<grid1(d->T, 4), 256, 0, s>>>(
+                static_cast<const bf16_t *>(d->hidden), d->w_layout == SPO_W_HV ? p.Wvh : static_cast<const bf16_t *>(d->W),
+                d->H, d->V, d->T, d->target, p.z_target);
     }
     token_loss_kernel<<<static_cast<unsigned>(p.nblk_tok), kTokThreads, 0, s>>>(
         p.part_max, p.part_sum, p.nsplit, p.T_pad, p.z_target, d->T, d->old_logp, d->mask, d->adv_norm,
@@ -602,8 +801,10 @@ struct BwdPlan {
     float *g, *dW_acc;
     bf16_t *WT, *Xb, *dZ, *Xs, *Ws, *Wvh;  // Xb: bf16 copy of the gathered rows of an fp32 hidden
     float *W32;  // [V,H] copy of an fp32 head given as [H,V]
-    int32_t *act_idx, *n_act, *tgt_c;  // active-token list, its length, per-chunk compact copies
-    float *lse_c, *g_c;
+    int32_t *act_idx, *n_act;  // active-token list, its length
+    float4 *tok;               // per-chunk records (g, -lse*log2e, target) of the gathered rows
+    int dx_split;              // parts the dHidden contraction is cut into (1: not split)
+    float *dx_part;            // their fp32 partial results [dx_split][Tc][H]
     void *Xc;
     size_t bytes;
 };
@@ -611,20 +812,23 @@ struct BwdPlan {
 static BwdPlan plan_bwd(const spo_pg_desc *d, int64_t chunk_tokens, void *ws, bool need_dw_acc) {
     BwdPlan p;
     const int64_t Tmax = round_up(std::max<int64_t>(d->T, 1), TL::BN);
-    int64_t tc = chunk_tokens > 0 ? chunk_tokens : kDefaultChunk;
-    p.Tc = std::min(round_up(tc, TL::BN), Tmax);
     p.T_pad = Tmax;
     p.V_pad = round_up(d->V, kBK);
     p.V_blk = round_up(d->V, TL::BM);
+    const int64_t tc = chunk_tokens > 0 ? round_up(chunk_tokens, TL::BN) : default_chunk_tokens(d->H, p.V_blk);
+    p.Tc = std::min(tc, Tmax);
     p.Kc = d->dtype == SPO_FP32 ? kSplitTerms * d->H : d->H;
     Arena a(ws);
     p.count = a.take<double>(1);
     p.g = a.take<float>(p.T_pad);
     p.act_idx = a.take<int32_t>(p.T_pad);
     p.n_act = a.take<int32_t>(1);
-    p.tgt_c = a.take<int32_t>(p.Tc);
-    p.lse_c = a.take<float>(p.Tc);
-    p.g_c = a.take<float>(p.Tc);
+    p.tok = a.take<float4>(p.Tc);
+    // dHidden has (Tc / 256) * ceil(H / 256) tiles; below three quarters of the chip's compute
+    // units the contraction over the vocabulary is cut into parts (H a multiple of 4 is given)
+    const int64_t dx_tiles = (p.Tc / TL::BN) * ceil_div(d->H, TL::BM);
+    p.dx_split = dx_tiles * 4 < kChipCUs * 3 ? static_cast<int>(std::min<int64_t>(8, kChipCUs / dx_tiles)) : 1;
+    p.dx_part = p.dx_split > 1 ? a.take<float>(static_cast<size_t>(p.dx_split) * p.Tc * d->H) : nullptr;
     p.Xc = a.take<char>(static_cast<size_t>(p.Tc) * d->H * (d->dtype == SPO_FP32 ? 4 : 2));
     p.WT = a.take<bf16_t>(static_cast<size_t>(d->H) * p.V_blk);   // [V_blk / 64][H][64]
     p.dZ = a.take<bf16_t>(static_cast<size_t>(p.Tc) * p.V_blk);  // [V_blk / 64][rows of the chunk][64]
@@ -660,12 +864,16 @@ static void launch_transpose(const SrcT *src, int64_t R, int64_t C, int64_t ld_s
 template <bool KMajor>
 static void launch_gemm(const bf16_t *A, int64_t lda, int64_t M, const bf16_t *B, int64_t ldb, int64_t N, int64_t K,
                         void *out, int64_t ldo, int out_dtype, int accumulate, const int32_t *n_act, int64_t row_base,
-                        int limit, const int32_t *row_map, int64_t a_blk_elems, int64_t b_blk_elems, hipStream_t s) {
+                        int limit, const int32_t *row_map, int64_t a_blk_elems, int64_t b_blk_elems, hipStream_t s,
+                        int nsplit = 1, float *partials = nullptr) {
     const TileOrder ord(ceil_div(M, TL::BM), ceil_div(N, TL::BN));
-    gemm_store_kernel<KMajor><<<static_cast<unsigned>(ord.blocks()), TL::NT, TL::LDS_BYTES, s>>>(
+    gemm_store_kernel<KMajor><<<static_cast<unsigned>(ord.blocks() * nsplit), TL::NT, TL::LDS_BYTES, s>>>(
         reinterpret_cast<const char *>(A), lda * 2, M, reinterpret_cast<const char *>(B), ldb * 2, N,
         static_cast<int>(K / kBK), out, ldo, out_dtype, accumulate, n_act, row_base, limit, row_map, a_blk_elems * 2,
-        b_blk_elems * 2);
+        b_blk_elems * 2, nsplit, partials);
+    if (nsplit > 1)
+        reduce_split_kernel<<<grid1(M * (N / 4)), 256, 0, s>>>(partials, nsplit, M, N, n_act, row_base, row_map, out, ldo,
+                                                               out_dtype);
 }
 
 int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float grad_loss, void *d_hidden,
@@ -678,6 +886,10 @@ int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float g
     const BwdPlan p = plan_bwd(d, chunk_tokens, ws, need_acc);
     if (ws_bytes < p.bytes) return SPO_EWORKSPACE;
     if ((rc = set_lds_limit())) return rc;
+    int dev = 0, ncu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || ncu < 1)
+        return SPO_EHIP;
     const int64_t H = d->H, V = d->V, T = d->T;
     float *dW32 = need_acc ? p.dW_acc : static_cast<float *>(d_W);
     if (T == 0) {
@@ -727,7 +939,7 @@ int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float g
             float *xc = static_cast<float *>(p.Xc);
             gather_chunk_kernel<float><<<static_cast<unsigned>(Tcp), 256, 0, s>>>(
                 static_cast<const float *>(d->hidden), H, p.act_idx, p.n_act, t0, Tcp, d->target, lse, p.g, xc,
-                p.tgt_c, p.lse_c, p.g_c);
+                p.tok);
             split_expand_kernel<<<grid1(Tcp * H), 256, 0, s>>>(xc, Tcp, H, p.Xs, 1);
             Xk = p.Xs;
             if (d_W) f32_to_bf16_kernel<<<grid1(Tcp * H), 256, 0, s>>>(xc, p.Xb, Tcp * H);
@@ -736,22 +948,24 @@ int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float g
             bf16_t *xc = static_cast<bf16_t *>(p.Xc);
             gather_chunk_kernel<bf16_t><<<static_cast<unsigned>(Tcp), 256, 0, s>>>(
                 static_cast<const bf16_t *>(d->hidden), H, p.act_idx, p.n_act, t0, Tcp, d->target, lse, p.g, xc,
-                p.tgt_c, p.lse_c, p.g_c);
+                p.tok);
             Xk = Xrows = xc;
         }
         {
+            // one persistent workgroup per compute unit (a workgroup fills a unit's LDS), in whole
+            // groups of 8 so that every XCD gets the same number
             const TileOrder ord(nVt, Tcp / TL::BN);
+            const int64_t wgs = std::min<int64_t>(std::max(ncu / 8, 1) * 8, ord.blocks());
             ScopedKernelTimer timer(kTimeRecompute, s);
-            recompute_dz_kernel<<<static_cast<unsigned>(ord.blocks()), TL::NT, TL::LDS_BYTES, s>>>(
+            recompute_dz_kernel<<<static_cast<unsigned>(wgs), TL::NT, TL::LDS_BYTES, s>>>(
                 reinterpret_cast<const char *>(Wk), p.Kc * 2, V, reinterpret_cast<const char *>(Xk), p.Kc * 2,
-                Tcp, static_cast<int>(p.Kc / kBK), p.tgt_c, p.lse_c, p.g_c, nVt, Tcp / TL::BN,
-                p.dZ, Tcp * kBlockK, p.n_act, t0);
+                Tcp, static_cast<int>(p.Kc / kBK), p.tok, nVt, Tcp / TL::BN, p.dZ, Tcp * kBlockK, p.n_act, t0);
         }
         if (d_hidden) {
             ScopedKernelTimer timer(kTimeDHidden, s);
             // both operands k-blocked over the vocabulary: a stage of a tile is 32 KiB contiguous
             launch_gemm<false>(p.dZ, kBlockK, Tcp, p.WT, kBlockK, H, p.V_pad, d_hidden, H, d_hidden_dtype, 0, p.n_act, t0,
-                               kLimitRows, p.act_idx + t0, Tcp * kBlockK, H * kBlockK, s);
+                               kLimitRows, p.act_idx + t0, Tcp * kBlockK, H * kBlockK, s, p.dx_split, p.dx_part);
         }
         if (d_W) {
             const int acc = (c > 0 || accumulate_dW) ? 1 : 0;

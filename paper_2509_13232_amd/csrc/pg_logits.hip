@@ -102,7 +102,8 @@ logits_row_lse_kernel(const T *__restrict__ logits, int64_t V, const int32_t *__
         for (int w = 1; w < kRowThreads / kWave; ++w) lse_merge(M, S, sm[w], ss[w]);
         row_max[t] = M;
         row_sum[t] = S;
-        z_target[t] = Vec<T>::get(row + target[t]);
+        const int64_t y = target[t];  // an id outside [0, V) gives NaN instead of a read out of bounds
+        z_target[t] = (y >= 0 && y < V) ? Vec<T>::get(row + y) : __builtin_nanf("");
     }
 }
 

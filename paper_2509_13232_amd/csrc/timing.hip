@@ -12,13 +12,23 @@ static std::mutex g_mu;
 static bool g_on = false;
 static std::vector<std::pair<hipEvent_t, hipEvent_t>> g_pairs[kTimeClasses];
 static hipEvent_t g_open[kTimeClasses];
+static std::vector<hipEvent_t> g_pool;  // events that have been read: reused, so that steady-state timing creates none
 
 bool timing_enabled() { return g_on; }
+
+static bool take_event(hipEvent_t *e) {
+    if (!g_pool.empty()) {
+        *e = g_pool.back();
+        g_pool.pop_back();
+        return true;
+    }
+    return hipEventCreate(e) == hipSuccess;
+}
 
 void timing_begin(int cls, hipStream_t s) {
     std::lock_guard<std::mutex> lk(g_mu);
     hipEvent_t a;
-    if (hipEventCreate(&a) != hipSuccess) return;
+    if (!take_event(&a)) return;
     (void)hipEventRecord(a, s);
     g_open[cls] = a;
 }
@@ -26,7 +36,7 @@ void timing_begin(int cls, hipStream_t s) {
 void timing_end(int cls, hipStream_t s) {
     std::lock_guard<std::mutex> lk(g_mu);
     hipEvent_t b;
-    if (!g_open[cls] || hipEventCreate(&b) != hipSuccess) return;
+    if (!g_open[cls] || !take_event(&b)) return;
     (void)hipEventRecord(b, s);
     g_pairs[cls].emplace_back(g_open[cls], b);
     g_open[cls] = nullptr;
@@ -53,8 +63,8 @@ extern "C" int spo_kernel_timing_read(float *ms, int32_t *launches) {
             if (hipEventSynchronize(p.second) != hipSuccess || hipEventElapsedTime(&t, p.first, p.second) != hipSuccess)
                 rc = SPO_EHIP;
             total += t;
-            (void)hipEventDestroy(p.first);
-            (void)hipEventDestroy(p.second);
+            g_pool.push_back(p.first);
+            g_pool.push_back(p.second);
         }
         ms[c] = total;
         launches[c] = static_cast<int32_t>(g_pairs[c].size());
