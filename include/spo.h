@@ -120,12 +120,16 @@ int spo_sample_prompts_static(const float *alpha, const float *beta, int64_t N, 
  *              sigma + eps_norm == 0 gives adv_norm = 0, not NaN.
  * use_baseline 0 selects the paper's "no baseline" variant (v = 0).
  * adv_raw      optional [B]; adv_norm [B]; stats optional [2] = (mu, sigma).
+ * info         optional int32[1]: 0, or 1 if some idx[k] lies outside [0, N).  Such an
+ *              id is never used as an index: its advantage is NaN, and so are the
+ *              batch statistics and every normalised value.
  * Statistics are accumulated in fp64 in a fixed order (bitwise reproducible).
- * Limits: 1 <= B < 2^31, idx[k] in [0, N) (not checked on the device).
+ * Limits: 1 <= B < 2^31.
  * ------------------------------------------------------------------------- */
 int spo_advantages(const float *alpha, const float *beta, int64_t N, const int32_t *idx,
                    const float *reward, int32_t B, int ddof, float eps_norm, int use_baseline,
-                   float *adv_raw, float *adv_norm, float *stats, spo_stream_t stream);
+                   float *adv_raw, float *adv_norm, float *stats, int32_t *info,
+                   spo_stream_t stream);
 
 /* Diagnostics of the unnormalised advantages that the paper's analysis tracks
  * (Experiments, "Signal Efficiency and Information Loss" and "Signal Stability and
@@ -147,18 +151,30 @@ int spo_advantage_diagnostics(const float *adv_raw, const float *reward, int32_t
  *              values are read as 0).
  * ids_unique   1: the caller guarantees that idx holds no repeated id (one
  *              response per prompt).  0: repeated ids are applied one after the
- *              other in batch order, as if the responses arrived in sequence.
+ *              other in batch order, as if the responses arrived in sequence
+ *              (needs ws); the cost is one pass over the batch per repeat of the
+ *              most repeated id, in a single workgroup.
  * n_obs        optional uint32[N] visit counters, incremented per observation.
  * v_prev_out   optional [B]: tracker mean right before observation k.
+ * info         optional int32[1], bits: 1 = some idx[k] lies outside [0, N) (that
+ *              observation is skipped, nothing is written for it, its v_prev_out is
+ *              NaN); 2 = ids_unique = 1 but an id repeats (only looked for when ws is
+ *              given; the entry of such an id then holds one of its updates).
+ * ws           spo_tracker_update_workspace_bytes(N) bytes, 256-byte aligned: a table
+ *              of one int32 per prompt.  Required for ids_unique = 0; with
+ *              ids_unique = 1 it is optional and only serves the repeat check.
  * Arithmetic: rho and the products are formed in fp64 and rounded once to fp32,
  * so rho_min = rho_max = 1 reproduces Beta posterior counts exactly.
- * Limits: 1 <= B < 2^31; ids_unique = 0 costs O(B^2) comparisons.
- * Errors: d_half <= 0, rho_min > rho_max, rho outside [0, 1] -> SPO_EINVAL.
+ * Limits: 1 <= B < 2^31.
+ * Errors: d_half <= 0, rho_min > rho_max, rho outside [0, 1] -> SPO_EINVAL;
+ * ids_unique = 0 without ws, or ws too small -> SPO_EWORKSPACE.
  * ------------------------------------------------------------------------- */
+size_t spo_tracker_update_workspace_bytes(int64_t N);
 int spo_tracker_update(float *alpha, float *beta, int64_t N, const int32_t *idx,
                        const float *reward, const float *kl, int32_t B, float d_half,
                        float rho_min, float rho_max, int ids_unique, uint32_t *n_obs,
-                       float *v_prev_out, spo_stream_t stream);
+                       float *v_prev_out, int32_t *info, void *ws, size_t ws_bytes,
+                       spo_stream_t stream);
 
 /* ---------------------------------------------------------------------------
  * The tracker in its moving-average form, for rewards that are not binary
@@ -176,7 +192,8 @@ int spo_tracker_update(float *alpha, float *beta, int64_t N, const int32_t *idx,
 int spo_tracker_update_ema(float *v_hat, float *n_eff, int64_t N, const int32_t *idx,
                            const float *reward, const float *kl, int32_t B, float d_half,
                            float rho_min, float rho_max, int ids_unique, uint32_t *n_obs,
-                           float *v_prev_out, spo_stream_t stream);
+                           float *v_prev_out, int32_t *info, void *ws, size_t ws_bytes,
+                           spo_stream_t stream);
 
 /* Tracker initialisation (Method, "Initialization"; Appendix "SPO
  * Initialization"): N0 = 1/(1 - rho_min), alpha0 = N0*v0, beta0 = N0*(1 - v0),

@@ -21,7 +21,8 @@ SPO_SAMPLE_STATIC_MAX_N = 1 << 20
 EXPORTS = (
     "spo_status_string", "spo_sample_prompts_workspace_bytes", "spo_sample_prompts",
     "spo_sample_prompts_static",
-    "spo_advantages", "spo_advantage_diagnostics", "spo_tracker_update", "spo_tracker_update_ema",
+    "spo_advantages", "spo_advantage_diagnostics", "spo_tracker_update_workspace_bytes", "spo_tracker_update",
+    "spo_tracker_update_ema",
     "spo_tracker_init",
     "spo_pg_loss_fwd_workspace_bytes", "spo_pg_loss_fwd",
     "spo_pg_loss_bwd_workspace_bytes", "spo_pg_loss_bwd",
@@ -70,11 +71,13 @@ def lib():
         L.spo_sample_prompts_static.restype = C.c_int
         L.spo_sample_prompts_static.argtypes = [vp, vp, i64, i32, f64, u64, u64, C.c_int, u32, vp, vp, vp]
         L.spo_advantages.restype = C.c_int
-        L.spo_advantages.argtypes = [vp, vp, i64, vp, vp, i32, C.c_int, f32, C.c_int, vp, vp, vp, vp]
+        L.spo_advantages.argtypes = [vp, vp, i64, vp, vp, i32, C.c_int, f32, C.c_int, vp, vp, vp, vp, vp]
         L.spo_advantage_diagnostics.restype = C.c_int
         L.spo_advantage_diagnostics.argtypes = [vp, vp, i32, f32, f32, vp, vp]
         L.spo_tracker_update.restype = C.c_int
-        L.spo_tracker_update.argtypes = [vp, vp, i64, vp, vp, vp, i32, f32, f32, f32, C.c_int, vp, vp, vp]
+        L.spo_tracker_update_workspace_bytes.restype = sz
+        L.spo_tracker_update_workspace_bytes.argtypes = [i64]
+        L.spo_tracker_update.argtypes = [vp, vp, i64, vp, vp, vp, i32, f32, f32, f32, C.c_int, vp, vp, vp, vp, sz, vp]
         L.spo_tracker_update_ema.restype = C.c_int
         L.spo_tracker_update_ema.argtypes = L.spo_tracker_update.argtypes
         L.spo_tracker_init.restype = C.c_int
@@ -181,8 +184,10 @@ def spo_sample_prompts_static(alpha, beta, B, eps_explore=0.05, seed=0, iteratio
 
 
 # --------------------------------------------------------------- advantages
-def spo_advantages(alpha, beta, idx, reward, ddof=0, eps_norm=0.0, use_baseline=True):
+def spo_advantages(alpha, beta, idx, reward, ddof=0, eps_norm=0.0, use_baseline=True, info=None):
+    """Returns (adv_raw, adv_norm, stats).  info: optional int32[1] tensor that receives the range flag."""
     B = reward.numel()
+    _want(info, torch.int32, "info", 1)
     _want(reward, torch.float32, "reward")
     if use_baseline:
         _want(alpha, torch.float32, "alpha")
@@ -194,7 +199,7 @@ def spo_advantages(alpha, beta, idx, reward, ddof=0, eps_norm=0.0, use_baseline=
     st = torch.empty(2, dtype=torch.float32, device=reward.device)
     _check(lib().spo_advantages(_ptr(alpha), _ptr(beta), N, _ptr(idx), _ptr(reward), B, int(ddof),
                                 float(eps_norm), int(bool(use_baseline)), _ptr(raw), _ptr(nrm), _ptr(st),
-                                _stream()), "spo_advantages")
+                                _ptr(info), _stream()), "spo_advantages")
     return raw, nrm, st
 
 
@@ -210,38 +215,39 @@ def spo_advantage_diagnostics(adv_raw, reward, tau_tight=1e-4, tau_loose=0.02):
 
 
 # ------------------------------------------------------------------ tracker
-def spo_tracker_update(alpha, beta, idx, reward, kl, d_half, rho_min, rho_max, ids_unique=True,
-                       n_obs=None, want_v_prev=False):
-    """Updates alpha and beta IN PLACE; returns v_prev[B] when asked."""
-    N, B = alpha.numel(), idx.numel()
-    _want(alpha, torch.float32, "alpha")
-    _want(beta, torch.float32, "beta", N)
+def _tracker_update(fn, name, a, b, idx, reward, kl, d_half, rho_min, rho_max, ids_unique, n_obs, want_v_prev,
+                    info, workspace, check_repeats):
+    N, B = a.numel(), idx.numel()
+    _want(a, torch.float32, "state[0]")
+    _want(b, torch.float32, "state[1]", N)
     _want(idx, torch.int32, "idx")
     _want(reward, torch.float32, "reward", B)
     _want(kl, torch.float32, "kl", B)
     _want(n_obs, torch.int32, "n_obs", N)
-    vprev = torch.empty(B, dtype=torch.float32, device=alpha.device) if want_v_prev else None
-    _check(lib().spo_tracker_update(_ptr(alpha), _ptr(beta), N, _ptr(idx), _ptr(reward), _ptr(kl), B,
-                                    float(d_half), float(rho_min), float(rho_max), int(bool(ids_unique)),
-                                    _ptr(n_obs), _ptr(vprev), _stream()), "spo_tracker_update")
+    _want(info, torch.int32, "info", 1)
+    vprev = torch.empty(B, dtype=torch.float32, device=a.device) if want_v_prev else None
+    ws = workspace
+    if ws is None and (not ids_unique or check_repeats):   # the table of one int32 per prompt
+        ws = _workspace(lib().spo_tracker_update_workspace_bytes(N), a.device)
+    _check(fn(_ptr(a), _ptr(b), N, _ptr(idx), _ptr(reward), _ptr(kl), B, float(d_half), float(rho_min),
+              float(rho_max), int(bool(ids_unique)), _ptr(n_obs), _ptr(vprev), _ptr(info), _ptr(ws),
+              0 if ws is None else ws.numel(), _stream()), name)
     return vprev
+
+
+def spo_tracker_update(alpha, beta, idx, reward, kl, d_half, rho_min, rho_max, ids_unique=True,
+                       n_obs=None, want_v_prev=False, info=None, workspace=None, check_repeats=False):
+    """Updates alpha and beta IN PLACE; returns v_prev[B] when asked.  info: optional int32[1] tensor
+    (bit 1: id out of range, bit 2: repeated id with ids_unique, looked for when check_repeats)."""
+    return _tracker_update(lib().spo_tracker_update, "spo_tracker_update", alpha, beta, idx, reward, kl, d_half,
+                           rho_min, rho_max, ids_unique, n_obs, want_v_prev, info, workspace, check_repeats)
 
 
 def spo_tracker_update_ema(v_hat, n_eff, idx, reward, kl, d_half, rho_min, rho_max, ids_unique=True,
-                           n_obs=None, want_v_prev=False):
+                           n_obs=None, want_v_prev=False, info=None, workspace=None, check_repeats=False):
     """Moving-average form: updates v_hat and n_eff IN PLACE; returns v_prev[B] when asked."""
-    N, B = v_hat.numel(), idx.numel()
-    _want(v_hat, torch.float32, "v_hat")
-    _want(n_eff, torch.float32, "n_eff", N)
-    _want(idx, torch.int32, "idx")
-    _want(reward, torch.float32, "reward", B)
-    _want(kl, torch.float32, "kl", B)
-    _want(n_obs, torch.int32, "n_obs", N)
-    vprev = torch.empty(B, dtype=torch.float32, device=v_hat.device) if want_v_prev else None
-    _check(lib().spo_tracker_update_ema(_ptr(v_hat), _ptr(n_eff), N, _ptr(idx), _ptr(reward), _ptr(kl), B,
-                                        float(d_half), float(rho_min), float(rho_max), int(bool(ids_unique)),
-                                        _ptr(n_obs), _ptr(vprev), _stream()), "spo_tracker_update_ema")
-    return vprev
+    return _tracker_update(lib().spo_tracker_update_ema, "spo_tracker_update_ema", v_hat, n_eff, idx, reward, kl,
+                           d_half, rho_min, rho_max, ids_unique, n_obs, want_v_prev, info, workspace, check_repeats)
 
 
 def spo_tracker_init(v0, rho_min):

@@ -44,17 +44,37 @@ __device__ __forceinline__ void apply(float &a, float &b, float r, double rho) {
     else observe(a, b, r, rho);
 }
 
-// One thread per observation; ids are unique, so every thread owns its entry.
+constexpr int32_t kNoOwner = 0x7fffffff;
+constexpr int kInfoRange = 1, kInfoRepeat = 2;  // bits of info[0]
+
+__global__ void __launch_bounds__(256) fill_slots_kernel(int32_t *__restrict__ slot, int64_t N) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i < N) slot[i] = kNoOwner;
+}
+
+__global__ void clear_info_kernel(int32_t *__restrict__ info) { info[0] = 0; }
+
+// One thread per observation; ids are unique, so every thread owns its entry.  An id outside
+// [0, N) is skipped and flagged.  With a slot table (all kNoOwner) a repeated id is flagged too:
+// every observation files its number under its id and the ones that find another there raise
+// the flag (the entries are left filed; the table is refilled before its next use).
 template <bool Ema>
 __global__ void __launch_bounds__(256)
-tracker_update_unique_kernel(float *__restrict__ alpha, float *__restrict__ beta,
+tracker_update_unique_kernel(float *__restrict__ alpha, float *__restrict__ beta, int64_t N,
                              const int32_t *__restrict__ idx, const float *__restrict__ reward,
                              const float *__restrict__ kl, int B, double d_half, double rho_min,
                              double rho_max, uint32_t *__restrict__ n_obs,
-                             float *__restrict__ v_prev) {
+                             float *__restrict__ v_prev, int32_t *__restrict__ info,
+                             int32_t *__restrict__ slot) {
     const int k = blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= B) return;
     const int64_t i = idx[k];
+    if (i < 0 || i >= N) {
+        if (info) atomicOr(&info[0], kInfoRange);
+        if (v_prev) v_prev[k] = __builtin_nanf("");
+        return;
+    }
+    if (slot && info && atomicExch(&slot[i], k) != kNoOwner) atomicOr(&info[0], kInfoRepeat);
     float a = alpha[i], b = beta[i];
     if (v_prev) v_prev[k] = mean_of<Ema>(a, b);
     apply<Ema>(a, b, reward[k], discount(kl[k], d_half, rho_min, rho_max));
@@ -63,31 +83,82 @@ tracker_update_unique_kernel(float *__restrict__ alpha, float *__restrict__ beta
     if (n_obs) n_obs[i] += 1u;
 }
 
-// Repeated ids: the thread of the FIRST occurrence of an id applies all of its
-// observations one after the other in batch order; other threads do nothing.
+// Repeated ids, applied one after the other in batch order.  One workgroup works in rounds: every
+// pending observation files its number under its id with an atomic minimum (slot table, all
+// kNoOwner on entry and again on exit); the observation that finds its own number there is the
+// earliest pending one of its id and is applied, by one thread, with no other thread touching that
+// entry in this round.  The number of rounds is the largest number of repeats of an id (8 for
+// batches that sample every prompt 8 times), the work per round the batch size; a batch larger
+// than 32768 observations is taken in windows of that many, in order.  The minimum does not
+// depend on the order of the atomics: the result is the same on every run.  Tracker entries and
+// slots are read and written with L2-coherent accesses, since a later round's thread must see
+// what an earlier round's thread wrote.
+constexpr int kRoundThreads = 1024, kRoundPer = 32;
+
 template <bool Ema>
-__global__ void __launch_bounds__(256)
-tracker_update_ordered_kernel(float *__restrict__ alpha, float *__restrict__ beta,
-                              const int32_t *__restrict__ idx, const float *__restrict__ reward,
-                              const float *__restrict__ kl, int B, double d_half, double rho_min,
-                              double rho_max, uint32_t *__restrict__ n_obs,
-                              float *__restrict__ v_prev) {
-    const int k = blockIdx.x * blockDim.x + threadIdx.x;
-    if (k >= B) return;
-    const int32_t id = idx[k];
-    for (int j = 0; j < k; ++j)
-        if (idx[j] == id) return;  // an earlier thread owns this id
-    float a = alpha[id], b = beta[id];
-    uint32_t seen = 0;
-    for (int j = k; j < B; ++j) {
-        if (idx[j] != id) continue;
-        if (v_prev) v_prev[j] = mean_of<Ema>(a, b);
-        apply<Ema>(a, b, reward[j], discount(kl[j], d_half, rho_min, rho_max));
-        ++seen;
+__global__ void __launch_bounds__(kRoundThreads)
+tracker_update_rounds_kernel(float *__restrict__ alpha, float *__restrict__ beta, int64_t N,
+                             const int32_t *__restrict__ idx, const float *__restrict__ reward,
+                             const float *__restrict__ kl, int B, double d_half, double rho_min,
+                             double rho_max, uint32_t *__restrict__ n_obs, float *__restrict__ v_prev,
+                             int32_t *__restrict__ info, int32_t *__restrict__ slot) {
+    __shared__ int pending_flag[2];
+    auto ld = [](const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+    auto st = [](float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+    if (threadIdx.x == 0) { pending_flag[0] = 0; pending_flag[1] = 0; }
+    __syncthreads();
+    for (int64_t w0 = 0; w0 < B; w0 += static_cast<int64_t>(kRoundThreads) * kRoundPer) {
+        // observation j of this thread in the window: k = w0 + j * kRoundThreads + tid
+        uint32_t pending = 0;
+        for (int j = 0; j < kRoundPer; ++j) {
+            const int64_t k = w0 + static_cast<int64_t>(j) * kRoundThreads + threadIdx.x;
+            if (k >= B) break;
+            const int64_t i = idx[k];
+            if (i < 0 || i >= N) {
+                if (info) atomicOr(&info[0], kInfoRange);
+                if (v_prev) v_prev[k] = __builtin_nanf("");
+            } else {
+                pending |= 1u << j;
+            }
+        }
+        for (int round = 0;; ++round) {
+            for (int j = 0; j < kRoundPer; ++j)
+                if (pending >> j & 1u) {
+                    const int k = static_cast<int>(w0 + static_cast<int64_t>(j) * kRoundThreads + threadIdx.x);
+                    atomicMin(&slot[idx[k]], k);
+                }
+            __threadfence();
+            __syncthreads();  // every claim of this round is filed
+            uint32_t won = 0;
+            for (int j = 0; j < kRoundPer; ++j)
+                if (pending >> j & 1u) {
+                    const int k = static_cast<int>(w0 + static_cast<int64_t>(j) * kRoundThreads + threadIdx.x);
+                    if (__hip_atomic_load(&slot[idx[k]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == k) won |= 1u << j;
+                }
+            __syncthreads();  // every claim has been read
+            for (int j = 0; j < kRoundPer; ++j)
+                if (won >> j & 1u) {
+                    const int k = static_cast<int>(w0 + static_cast<int64_t>(j) * kRoundThreads + threadIdx.x);
+                    const int32_t i = idx[k];
+                    __hip_atomic_store(&slot[i], kNoOwner, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    float a = ld(&alpha[i]), b = ld(&beta[i]);
+                    if (v_prev) v_prev[k] = mean_of<Ema>(a, b);
+                    apply<Ema>(a, b, reward[k], discount(kl[k], d_half, rho_min, rho_max));
+                    st(&alpha[i], a);
+                    st(&beta[i], b);
+                    if (n_obs) atomicAdd(&n_obs[i], 1u);
+                }
+            pending &= ~won;
+            int *flag = &pending_flag[round & 1];
+            if (pending) *flag = 1;
+            __threadfence();
+            __syncthreads();  // the slots are clear again, the updates are visible, the flag is complete
+            const bool again = *flag != 0;
+            if (threadIdx.x == 0) pending_flag[(round + 1) & 1] = 0;
+            __syncthreads();
+            if (!again) break;
+        }
     }
-    alpha[id] = a;
-    beta[id] = b;
-    if (n_obs) n_obs[id] += seen;
 }
 
 __global__ void __launch_bounds__(256)
@@ -109,17 +180,24 @@ __global__ void __launch_bounds__(kAdvThreads)
 advantages_kernel(const float *__restrict__ alpha, const float *__restrict__ beta,
                   const int32_t *__restrict__ idx, const float *__restrict__ reward, int B, int ddof,
                   double eps_norm, int use_baseline, float *__restrict__ adv_raw,
-                  float *__restrict__ adv_norm, float *__restrict__ stats) {
+                  float *__restrict__ adv_norm, float *__restrict__ stats, int64_t N, int32_t *__restrict__ info) {
     __shared__ double scratch[kAdvThreads / kWave];
+    // an id outside [0, N) reads nothing: its baseline is NaN (so are the batch statistics) and it is flagged
     auto raw = [&](int k) -> double {
         double v = 0.0;
         if (use_baseline) {
             const int64_t i = idx[k];
+            if (i < 0 || i >= N) {
+                if (info) info[0] = kInfoRange;
+                return __builtin_nan("");
+            }
             const double a = alpha[i];
             v = beta ? a / (a + static_cast<double>(beta[i])) : a;
         }
         return static_cast<double>(reward[k]) - v;
     };
+    if (info && threadIdx.x == 0) info[0] = 0;
+    __syncthreads();
     double s = 0.0;
     for (int k = threadIdx.x; k < B; k += kAdvThreads) {
         const double a = raw(k);
@@ -188,39 +266,53 @@ extern "C" int spo_advantage_diagnostics(const float *adv_raw, const float *rewa
     return launch_status();
 }
 
+static size_t slot_table_bytes(int64_t N) { return align_up(static_cast<size_t>(N) * sizeof(int32_t), 256); }
+
 template <bool Ema>
 static int tracker_update_launch(float *alpha, float *beta, int64_t N, const int32_t *idx,
                                  const float *reward, const float *kl, int32_t B, float d_half,
                                  float rho_min, float rho_max, int ids_unique, uint32_t *n_obs,
-                                 float *v_prev_out, spo_stream_t stream) {
+                                 float *v_prev_out, int32_t *info, void *ws, size_t ws_bytes,
+                                 spo_stream_t stream) {
     if (!alpha || !beta || !idx || !reward || !kl) return SPO_ENULL;
     if (N < 1 || N >= (int64_t(1) << 31) || B < 1) return SPO_EINVAL;
     if (!(d_half > 0.0f) || !(rho_min >= 0.0f) || !(rho_max <= 1.0f) || !(rho_min <= rho_max))
         return SPO_EINVAL;
-    const int threads = 256, blocks = (B + threads - 1) / threads;
-    if (ids_unique)
-        tracker_update_unique_kernel<Ema><<<blocks, threads, 0, as_stream(stream)>>>(
-            alpha, beta, idx, reward, kl, B, d_half, rho_min, rho_max, n_obs, v_prev_out);
-    else
-        tracker_update_ordered_kernel<Ema><<<blocks, threads, 0, as_stream(stream)>>>(
-            alpha, beta, idx, reward, kl, B, d_half, rho_min, rho_max, n_obs, v_prev_out);
+    if (ws && (reinterpret_cast<uintptr_t>(ws) % 256 != 0)) return SPO_EINVAL;
+    if ((ws || !ids_unique) && (!ws || ws_bytes < slot_table_bytes(N))) return SPO_EWORKSPACE;
+    hipStream_t s = as_stream(stream);
+    int32_t *slot = static_cast<int32_t *>(ws);
+    if (info) clear_info_kernel<<<1, 1, 0, s>>>(info);
+    if (slot) fill_slots_kernel<<<static_cast<unsigned>(ceil_div(N, 256)), 256, 0, s>>>(slot, N);
+    if (ids_unique) {
+        const int threads = 256, blocks = (B + threads - 1) / threads;
+        tracker_update_unique_kernel<Ema><<<blocks, threads, 0, s>>>(alpha, beta, N, idx, reward, kl, B, d_half, rho_min,
+                                                                      rho_max, n_obs, v_prev_out, info, slot);
+    } else {
+        tracker_update_rounds_kernel<Ema><<<1, kRoundThreads, 0, s>>>(alpha, beta, N, idx, reward, kl, B, d_half, rho_min,
+                                                                       rho_max, n_obs, v_prev_out, info, slot);
+    }
     return launch_status();
 }
+
+extern "C" size_t spo_tracker_update_workspace_bytes(int64_t N) { return N < 1 ? 0 : slot_table_bytes(N); }
 
 extern "C" int spo_tracker_update(float *alpha, float *beta, int64_t N, const int32_t *idx,
                                   const float *reward, const float *kl, int32_t B, float d_half,
                                   float rho_min, float rho_max, int ids_unique, uint32_t *n_obs,
-                                  float *v_prev_out, spo_stream_t stream) {
+                                  float *v_prev_out, int32_t *info, void *ws, size_t ws_bytes,
+                                  spo_stream_t stream) {
     return tracker_update_launch<false>(alpha, beta, N, idx, reward, kl, B, d_half, rho_min, rho_max,
-                                        ids_unique, n_obs, v_prev_out, stream);
+                                        ids_unique, n_obs, v_prev_out, info, ws, ws_bytes, stream);
 }
 
 extern "C" int spo_tracker_update_ema(float *v_hat, float *n_eff, int64_t N, const int32_t *idx,
                                       const float *reward, const float *kl, int32_t B, float d_half,
                                       float rho_min, float rho_max, int ids_unique, uint32_t *n_obs,
-                                      float *v_prev_out, spo_stream_t stream) {
+                                      float *v_prev_out, int32_t *info, void *ws, size_t ws_bytes,
+                                      spo_stream_t stream) {
     return tracker_update_launch<true>(v_hat, n_eff, N, idx, reward, kl, B, d_half, rho_min, rho_max,
-                                       ids_unique, n_obs, v_prev_out, stream);
+                                       ids_unique, n_obs, v_prev_out, info, ws, ws_bytes, stream);
 }
 
 extern "C" int spo_tracker_init(const float *v0, int64_t N, float rho_min, float *alpha,
@@ -238,12 +330,12 @@ extern "C" int spo_tracker_init(const float *v0, int64_t N, float rho_min, float
 extern "C" int spo_advantages(const float *alpha, const float *beta, int64_t N, const int32_t *idx,
                               const float *reward, int32_t B, int ddof, float eps_norm,
                               int use_baseline, float *adv_raw, float *adv_norm, float *stats,
-                              spo_stream_t stream) {
+                              int32_t *info, spo_stream_t stream) {
     if (!reward || !adv_norm) return SPO_ENULL;
     if (use_baseline && (!alpha || !idx)) return SPO_ENULL;
     if (B < 1 || (use_baseline && N < 1) || ddof < 0 || ddof > 1 || !(eps_norm >= 0.0f))
         return SPO_EINVAL;
     advantages_kernel<<<1, kAdvThreads, 0, as_stream(stream)>>>(
-        alpha, beta, idx, reward, B, ddof, eps_norm, use_baseline, adv_raw, adv_norm, stats);
+        alpha, beta, idx, reward, B, ddof, eps_norm, use_baseline, adv_raw, adv_norm, stats, N, info);
     return launch_status();
 }

@@ -71,7 +71,8 @@ def test_fused_bf16_matches_oracle(spo, oracle, w_layout, w_scale, mask_frac):
     onehot_dx = g[:, None] * Wd[case.target]
     soft_ref = rb["d_hidden"] - onehot_dx
     soft_gpu = f64(dx) - onehot_dx
-    bound = GRAD_TOL * np.linalg.norm(soft_ref) + 2.0 ** -8 * np.linalg.norm(onehot_dx)
+    # (a target entry of dZ is rounded to bf16 once: at most 2^-9 of it)
+    bound = GRAD_TOL * np.linalg.norm(soft_ref) + 1.1 * 2.0 ** -9 * np.linalg.norm(onehot_dx)
     assert np.linalg.norm(soft_gpu - soft_ref) <= bound
     if w_scale > 1.0:   # peaked softmax: the softmax part is as large as the target part
         assert np.linalg.norm(soft_ref) > 0.3 * np.linalg.norm(onehot_dx)

@@ -101,6 +101,83 @@ def test_tracker_update_with_repeated_ids_is_sequential(spo, oracle):
     assert np.array_equal(nobs.cpu().numpy(), np.bincount(idx, minlength=cfg.N))
 
 
+@pytest.mark.parametrize("B,G,N", [(16384, 8, 1 << 20), (40000, 3, 20000), (512, 512, 64)])
+def test_tracker_update_of_batches_that_repeat_every_prompt(spo, oracle, B, G, N):
+    # batch extensions that sample every prompt G times (Appendix "Batch Extensions"): B observations,
+    # each id G times in shuffled order; also a batch beyond one window of the kernel (40000) and one
+    # id repeated 512 times (as many rounds as observations).  Values 1e-5, visit counters exact, and
+    # the slot table the kernel borrows is handed back clean (a second call gives the same answer).
+    say(f"tracker_update B={B}, every id {G} times, N={N}")
+    rng = np.random.default_rng([B, G])
+    B = B // G * G
+    ids = rng.choice(N, B // G, replace=False).astype(np.int32)
+    idx = rng.permutation(np.repeat(ids, G)).astype(np.int32)
+    a = rng.uniform(0.5, 50, N).astype(np.float32)
+    b = rng.uniform(0.5, 50, N).astype(np.float32)
+    r = (rng.random(B) < 0.4).astype(np.float32)
+    kl = rng.exponential(0.02, B).astype(np.float32)
+    ea, eb, ev, _ = oracle.tracker_update(a, b, idx, r, kl, 0.25, 0.875, 0.96)
+    ws = torch.empty(spo.lib().spo_tracker_update_workspace_bytes(N), dtype=torch.uint8, device="cuda")
+    for _ in range(2):
+        ga, gb = dev(a), dev(b)
+        nobs = torch.zeros(N, dtype=torch.int32, device="cuda")
+        info = torch.full((1,), 7, dtype=torch.int32, device="cuda")
+        gv = spo.spo_tracker_update(ga, gb, dev(idx), dev(r), dev(kl), 0.25, 0.875, 0.96, ids_unique=False,
+                                    n_obs=nobs, want_v_prev=True, info=info, workspace=ws)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(ga.cpu().numpy(), ea, rtol=RTOL)
+        np.testing.assert_allclose(gb.cpu().numpy(), eb, rtol=RTOL)
+        np.testing.assert_allclose(gv.cpu().numpy(), ev, rtol=RTOL)
+        assert np.array_equal(nobs.cpu().numpy(), np.bincount(idx, minlength=N))
+        assert info.item() == 0
+
+
+def test_ids_out_of_range_or_repeated_are_flagged_not_followed(spo, oracle):
+    say("tracker_update / advantages: ids outside the table, repeats under ids_unique")
+    N, B = 1000, 64
+    rng = np.random.default_rng(3)
+    a = rng.uniform(0.5, 50, N).astype(np.float32)
+    b = rng.uniform(0.5, 50, N).astype(np.float32)
+    idx = rng.choice(N, B, replace=False).astype(np.int32)
+    r = (rng.random(B) < 0.5).astype(np.float32)
+    kl = rng.uniform(0, 0.05, B).astype(np.float32)
+    bad = idx.copy()
+    bad[[3, 40]] = [N, -1]
+    good = np.ones(B, bool)
+    good[[3, 40]] = False
+    ea, eb, ev, _ = oracle.tracker_update(a, b, idx[good], r[good], kl[good], 0.25, 0.875, 0.96)
+    for unique in (True, False):
+        ga, gb = dev(a), dev(b)
+        info = torch.zeros(1, dtype=torch.int32, device="cuda")
+        gv = spo.spo_tracker_update(ga, gb, dev(bad), dev(r), dev(kl), 0.25, 0.875, 0.96, ids_unique=unique,
+                                    want_v_prev=True, info=info)
+        torch.cuda.synchronize()
+        assert info.item() == 1                                            # out of range, nothing else
+        np.testing.assert_allclose(ga.cpu().numpy(), ea, rtol=RTOL)       # the other observations are applied
+        np.testing.assert_allclose(gb.cpu().numpy(), eb, rtol=RTOL)
+        v = gv.cpu().numpy()
+        assert np.isnan(v[~good]).all()
+        np.testing.assert_allclose(v[good], ev, rtol=RTOL)
+    # advantages: the flag, NaN for the response, no read outside the table
+    info = torch.zeros(1, dtype=torch.int32, device="cuda")
+    raw, nrm, _ = spo.spo_advantages(dev(a), dev(b), dev(bad), dev(r), info=info)
+    torch.cuda.synchronize()
+    assert info.item() == 1 and np.isnan(raw.cpu().numpy()[~good]).all() and np.isfinite(raw.cpu().numpy()[good]).all()
+    raw, nrm, _ = spo.spo_advantages(dev(a), dev(b), dev(idx), dev(r), info=info)
+    torch.cuda.synchronize()
+    assert info.item() == 0 and np.isfinite(nrm.cpu().numpy()).all()
+    # a repeated id under ids_unique = 1 is found when the table is there to look
+    rep = idx.copy()
+    rep[10] = rep[50]
+    info = torch.zeros(1, dtype=torch.int32, device="cuda")
+    spo.spo_tracker_update(dev(a), dev(b), dev(rep), dev(r), dev(kl), 0.25, 0.875, 0.96, info=info, check_repeats=True)
+    torch.cuda.synchronize()
+    assert info.item() == 2
+    spo.spo_tracker_update(dev(a), dev(b), dev(idx), dev(r), dev(kl), 0.25, 0.875, 0.96, info=info, check_repeats=True)
+    torch.cuda.synchronize()
+    assert info.item() == 0
+
+
 def test_tracker_init(spo, oracle):
     say("tracker_init")
     v0 = (np.random.default_rng(0).integers(0, 9, 1000) / 8.0).astype(np.float32)
