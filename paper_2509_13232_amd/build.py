@@ -25,9 +25,14 @@ def _hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = [_hipcc(), *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+# host-side sanitizers (the device code cannot carry them): each -fsanitize= follows its own -Xarch_host
+SAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+             "-Xarch_host", "-fno-sanitize-recover=all", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+
+
+def _compile(src: str, obj_dir: str = OBJ, extra=()) -> str:
+    obj = os.path.join(obj_dir, src.replace(".hip", ".o"))
+    cmd = [_hipcc(), *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         sys.stderr.write(r.stdout + r.stderr)
@@ -47,6 +52,28 @@ def build(verbose: bool = False) -> str:
     if verbose:
         print("built", LIB)
     return LIB
+
+
+def build_sanitized_driver(driver_cpp: str, exe: str) -> str:
+    """Links `driver_cpp` with the library's sources, host code built with AddressSanitizer and
+    UndefinedBehaviorSanitizer, into the executable `exe` (a test aid: argument checks under sanitizers)."""
+    obj_dir = OBJ + "_san"
+    os.makedirs(obj_dir, exist_ok=True)
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
+        objs = list(ex.map(lambda src: _compile(src, obj_dir, SAN_FLAGS), SOURCES))
+    drv_obj = os.path.join(obj_dir, "driver.o")
+    steps = [
+        ["g++", "-O1", "-g", "-std=c++17", "-I" + INCLUDE, "-fsanitize=address", "-fsanitize=undefined",
+         "-fno-sanitize-recover=all", "-fno-omit-frame-pointer", "-c", driver_cpp, "-o", drv_obj],
+        # the sanitizer runtimes come from the host compiler that built the driver; hipcc adds the HIP runtime
+        [_hipcc(), "--offload-arch=gfx950", drv_obj, *objs, "-o", exe, "-fsanitize=address", "-fsanitize=undefined"],
+    ]
+    for cmd in steps:
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            sys.stderr.write((r.stdout + r.stderr)[-3000:])
+            raise RuntimeError("sanitized build failed: " + " ".join(cmd[:2]))
+    return exe
 
 
 if __name__ == "__main__":

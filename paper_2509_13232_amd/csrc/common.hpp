@@ -18,14 +18,15 @@ static inline int launch_status() {
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 __host__ __device__ static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-// Bump allocator over the caller's workspace; every block 256-byte aligned.
+// Bump allocator over the caller's workspace; every block 256-byte aligned.  With a NULL
+// base it only adds up sizes (the workspace queries) and hands out NULL.
 struct Arena {
     char *base;
     size_t used;
     explicit Arena(void *p) : base(static_cast<char *>(p)), used(0) {}
     template <typename T>
     T *take(size_t count) {
-        T *p = reinterpret_cast<T *>(base + used);
+        T *p = base ? reinterpret_cast<T *>(base + used) : nullptr;
         used += align_up(count * sizeof(T), 256);
         return p;
     }
