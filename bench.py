@@ -12,8 +12,6 @@ responses (~280k tokens).  Prints ONE JSON line.
 from __future__ import annotations
 
 import argparse
-import glob
-import hashlib
 import json
 import os
 import re
@@ -35,10 +33,8 @@ def log(*a):
 
 def kernel_source_digest() -> str:
     """Digest of the kernel sources: a traffic profile is only quoted for the kernels it was taken from."""
-    h = hashlib.sha256()
-    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2509_13232_amd", "csrc", "*.h*"))):
-        h.update(open(f, "rb").read())
-    return h.hexdigest()[:16]
+    from paper_2509_13232_amd.build import source_digest
+    return source_digest()
 
 
 def profiled_traffic(workload: str, chunk_tokens: int):

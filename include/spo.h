@@ -78,7 +78,13 @@ const char *spo_status_string(int status);
  *               attempt number used.  If every weight is zero (eps_explore = 0
  *               and every v_i is 0 or 1) nothing can be drawn: all entries are
  *               -1 and info[0] = 1.
- * max_attempts  bound on attempts per slot (0 selects 2^20).
+ * max_attempts  bound on attempts per slot (0 selects 65536).  Without replacement the
+ *               draw runs in one workgroup, one sweep over the B slots per attempt
+ *               level (about 2 us each): a batch that takes most of the prompts
+ *               with non-zero weight needs many levels for its last slots (about
+ *               N ln N draws to collect the last of N equal weights), so such a
+ *               call can take max_attempts sweeps before it gives up; info[0] and
+ *               info[1] tell.
  * ws            spo_sample_prompts_workspace_bytes(N, B) bytes, 256-byte aligned.
  * Limits: 1 <= N < 2^31, 1 <= B <= 16384 (replace = 0) or B < 2^31 (replace = 1).
  * ------------------------------------------------------------------------- */

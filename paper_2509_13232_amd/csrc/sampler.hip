@@ -279,7 +279,7 @@ static int sample_launch(const float *alpha, const float *beta, int64_t N, int32
                          uint64_t seed, uint64_t iteration, int replace, uint32_t max_attempts,
                          int32_t *idx_out, int32_t *info, void *ws, hipStream_t s) {
     const SamplerWorkspace w = sampler_layout(ws, N);
-    if (max_attempts == 0) max_attempts = 1u << 20;
+    if (max_attempts == 0) max_attempts = 1u << 16;  // a sweep per attempt level: bounds a hopeless draw to ~0.1 s
     const int64_t nblocks = ceil_div(N, kScanItems);
     weight_block_sums_kernel<<<static_cast<unsigned>(nblocks), kScanThreads, 0, s>>>(alpha, beta, N, eps_explore, w.block_sums);
     scan_block_sums_kernel<<<1, kScanThreads, 0, s>>>(w.block_sums, nblocks, w.total);
