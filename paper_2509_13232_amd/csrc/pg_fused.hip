@@ -180,9 +180,11 @@ __device__ __forceinline__ int64_t active_rows(const int32_t *n_act, int64_t row
 
 // Rows [row_base, row_base + rows) of the compact order as contiguous copies: the hidden
 // states (Xc[r] = X[act_idx[row_base + r]]) and, packed into one 16-byte record per row, the
-// per-token scalars the recompute needs: tok[r] = (g, -lse * log2(e), target as bits, 0).
-// Rows past the last active token are filled with zeros and (0, -huge, -1, 0): scale zero and
-// an exponent that underflows, so that 0 * p stays 0.  One workgroup per row.
+// per-token scalars the recompute needs: tok[r] = (|g|, log2|g| - lse * log2(e), target with the
+// sign of g in the top bit (set: g > 0), 0): the gradient's softmax part -g * p is then
+// -sign(g) * exp2(z * log2(e) + tok.y), one multiply-add and one exponential per logit.
+// Rows past the last active token are filled with zeros and (0, -inf, no target): every
+// exponential underflows to an exact zero.  One workgroup per row.
 template <typename T_>
 __global__ void __launch_bounds__(256)
 gather_chunk_kernel(const T_ *__restrict__ X, int64_t H, const int32_t *__restrict__ act_idx,
@@ -196,9 +198,12 @@ gather_chunk_kernel(const T_ *__restrict__ X, int64_t H, const int32_t *__restri
     const uint4 *in = reinterpret_cast<const uint4 *>(X + src * H);
     uint4 *out = reinterpret_cast<uint4 *>(Xc + r * H);
     for (int i = threadIdx.x; i < n16; i += 256) out[i] = live ? in[i] : make_uint4(0u, 0u, 0u, 0u);
-    if (threadIdx.x == 0)
-        tok[r] = live ? make_float4(g[src], -lse[src] * kLog2e, __int_as_float(target[src]), 0.0f)
-                      : make_float4(0.0f, kNegBig, __int_as_float(-1), 0.0f);
+    if (threadIdx.x == 0) {
+        const float gs = live ? g[src] : 0.0f;
+        const uint32_t ts = live ? (static_cast<uint32_t>(target[src]) & 0x7fffffffu) | (gs > 0.0f ? 0x80000000u : 0u)
+                                 : 0x7fffffffu;
+        tok[r] = make_float4(fabsf(gs), live ? log2f(fabsf(gs)) - lse[src] * kLog2e : -INFINITY, __uint_as_float(ts), 0.0f);
+    }
 }
 
 // ----------------------------------------------------------------------------
@@ -251,12 +256,45 @@ target_logit_kernel(const T_ *__restrict__ X, const T_ *__restrict__ Wvh, int64_
 // ----------------------------------------------------------------------------
 // Tile rows (m) are vocabulary entries, tile columns (n) are tokens, so that each
 // lane owns FN tokens and reduces over the vocabulary inside its own registers.
-// Workgroup (token tile jt, vocabulary split r) walks the vocabulary tiles of its
-// split.  Ids equal mod 8 run on the same XCD and share its L2: there, 32 consecutive
-// workgroups are a patch of 4 token tiles x 8 splits (each hidden-state panel feeds 8
-// of them, each head tile 4), and the patches of one group of 4 token tiles follow
-// one another.  More than 8 splits shorten a workgroup's sweep: workgroups that share
-// lines then have less time to drift apart before new ones start in step.
+
+// Workgroup -> (token tile, vocabulary split) of the two kernels that form logits (the forward
+// sweep and the backward's recompute): a workgroup keeps its token tile and walks the vocabulary
+// tiles of its split.  Ids equal mod 8 run on the same XCD and share its L2: there, 32
+// consecutive workgroups are a patch of 4 token tiles x 8 splits (each hidden-state panel feeds
+// 8 of them, each head tile 4), and the eight XCDs work on the same splits of different token
+// tiles at about the same time, so a head tile fetched from memory serves 32 token tiles out of
+// the Infinity Cache.  (A 4 x 8 patch of tiles walked along the vocabulary, every head tile used by
+// one XCD only, made the recompute 3.6 % slower.)  More than 8 splits shorten a workgroup's
+// sweep: workgroups that share lines then have less time to drift apart.
+struct SweepMap {
+    int nsplit;
+    int64_t nTt, nVt, per_xcd;
+    __host__ __device__ SweepMap(int64_t token_tiles, int64_t vocab_tiles) : nTt(token_tiles), nVt(vocab_tiles) {
+        int64_t ns = (2048 + (nTt > 0 ? nTt : 1) - 1) / (nTt > 0 ? nTt : 1);  // small batches: more splits fill the chip
+        ns = ns < kSweepSplits ? kSweepSplits : ns;
+        ns = ns < nVt ? ns : nVt;
+        nsplit = static_cast<int>(ns >= 8 ? ns / 8 * 8 : ns);  // whole groups of 8 splits whenever there are 8
+        const int64_t x = (nTt + 7) / 8;
+        per_xcd = nsplit % 8 == 0 ? (x + 3) / 4 * 4 : x;  // whole patches of 4 when the splits come in groups of 8
+    }
+    __host__ __device__ int64_t blocks() const { return per_xcd * 8 * nsplit; }
+    // token tile jt and split of workgroup bid; false past the last token tile
+    __device__ bool tile(int64_t bid, int &split, int64_t &jt) const {
+        const int64_t xcd = bid & 7, q = bid >> 3;
+        if (nsplit % 8 == 0) {
+            const int groups = nsplit / 8, w = static_cast<int>(q & 31);
+            const int64_t patch = q >> 5;
+            split = static_cast<int>(patch % groups) * 8 + (w & 7);
+            jt = ((patch / groups) * 4 + (w >> 3)) * 8 + xcd;
+        } else {  // small problems: all splits of a token tile side by side
+            split = static_cast<int>(q % nsplit);
+            jt = (q / nsplit) * 8 + xcd;
+        }
+        return jt < nTt;
+    }
+    __device__ int64_t first_tile(int split) const { return split * nVt / nsplit; }
+};
+
 constexpr int kSweepLds = TL::LDS_BYTES + TL::NT * 32;  // operand stages + the per-thread running state
 
 __global__ void __launch_bounds__(TL::NT)
@@ -264,21 +302,12 @@ fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const
                  int64_t ldx_bytes, int64_t T, int KT, int nsplit, int64_t nTt, int64_t nVt, int64_t T_pad,
                  float *__restrict__ part_max, float *__restrict__ part_sum) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    const int64_t bid = blockIdx.x, xcd = bid & 7, q = bid >> 3;
+    const SweepMap map(nTt, nVt);  // map.nsplit == nsplit: the host sized the partial results with the same map
     int split;
     int64_t jt;
-    if (nsplit % 8 == 0) {
-        const int groups = nsplit / 8, w = static_cast<int>(q & 31);
-        const int64_t patch = q >> 5;
-        split = static_cast<int>(patch % groups) * 8 + (w & 7);
-        jt = ((patch / groups) * 4 + (w >> 3)) * 8 + xcd;
-    } else {  // small problems: all splits of a token tile side by side
-        split = static_cast<int>(q % nsplit);
-        jt = (q / nsplit) * 8 + xcd;
-    }
-    if (jt >= nTt) return;
+    if (!map.tile(blockIdx.x, split, jt)) return;
     const int64_t n0 = jt * TL::BN;
-    const int64_t vt0 = split * nVt / nsplit, vt1 = (split + 1) * nVt / nsplit;
+    const int64_t vt0 = map.first_tile(split), vt1 = map.first_tile(split + 1);
     const int lane = threadIdx.x & 63;
 
     // Running (maximum, sum of exponentials) of this lane's FN tokens.  Between tiles they wait in
@@ -384,24 +413,18 @@ fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const
 // or after the number of active rows of this chunk (device value n_act[0] - row_base) are
 // skipped altogether.
 //
-// Persistent workgroups, one per compute unit: workgroup (XCD x, slot j) computes tile j of
-// every patch of 4 x 8 tiles that TileOrder gives XCD x, one after the other.  The gradients
-// go from the accumulators to memory without a detour through LDS.
+// Workgroups map to (token tile, vocabulary split) as in the forward sweep (SweepMap).  The
+// gradients go from the accumulators to memory without a detour through LDS.
 
-// 4 x 4 transpose of 32-bit values across the four groups of 16 lanes of a wavefront: on
-// return register q of lane group g holds what register g of lane group q held.
-// v_permlane32_swap(a, b) exchanges the upper 32 lanes of a with the lower 32 lanes of b,
-// v_permlane16_swap(a, b) the odd groups of 16 lanes of a with the even groups of b.
-__device__ __forceinline__ void transpose_lane_groups(uint32_t &r0, uint32_t &r1, uint32_t &r2, uint32_t &r3) {
+// Exchange between neighbouring groups of 16 lanes: v_permlane16_swap(a, b) swaps the odd groups
+// of a with the even groups of b.  With a, b the values a lane holds for two consecutive MFMA
+// blocks q, q+1, lane group g ends up with (in a, b) the values of block q + (g & 1) from lane
+// groups (g & 2) and (g & 2) + 1.
+__device__ __forceinline__ void swap_lane_groups(uint32_t &a, uint32_t &b) {
     typedef unsigned v2u __attribute__((ext_vector_type(2)));
-    v2u t = __builtin_amdgcn_permlane32_swap(r0, r2, false, false);
-    r0 = t.x; r2 = t.y;
-    t = __builtin_amdgcn_permlane32_swap(r1, r3, false, false);
-    r1 = t.x; r3 = t.y;
-    t = __builtin_amdgcn_permlane16_swap(r0, r1, false, false);
-    r0 = t.x; r1 = t.y;
-    t = __builtin_amdgcn_permlane16_swap(r2, r3, false, false);
-    r2 = t.x; r3 = t.y;
+    const v2u t = __builtin_amdgcn_permlane16_swap(a, b, false, false);
+    a = t.x;
+    b = t.y;
 }
 
 __global__ void __launch_bounds__(TL::NT)
@@ -412,24 +435,13 @@ recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V,
     extern __shared__ __attribute__((aligned(16))) char lds[];
     static_assert(TL::BM % kBlockK == 0 && kBlockK == 4 * TL::MI && TL::FM % 4 == 0,
                   "a block of dZ is four MFMA blocks of vocabulary rows");
-    const TileOrder ord(nVt, nTt);
     const int act = static_cast<int>(active_rows(n_act, row_base, T_valid));
-    const int xcd = blockIdx.x & 7;
-    const int slot = blockIdx.x >> 3, nslot = gridDim.x >> 3, n_items = static_cast<int>(ord.blocks() >> 3);
-    // item i of this XCD is what TileOrder calls workgroup i * 8 + xcd; first valid item at or after `item`
-    auto advance = [&](int item, int &tm, int &tn) {
-        for (; item < n_items; item += nslot) {
-            int64_t a, b;
-            if (ord.tile(static_cast<int64_t>(item) * 8 + xcd, a, b) && b * TL::BN < act) {
-                tm = static_cast<int>(a);
-                tn = static_cast<int>(b);
-                break;
-            }
-        }
-        return item;
-    };
-    int tm = 0, tn = 0;
-    int item = advance(slot, tm, tn);
+    const SweepMap map(nTt, nVt);
+    int split;
+    int64_t jt;
+    if (!map.tile(blockIdx.x, split, jt) || jt * TL::BN >= act) return;  // past the last active token
+    const int tn = static_cast<int>(jt);
+    const int vt0 = static_cast<int>(map.first_tile(split)), vt1 = static_cast<int>(map.first_tile(split + 1));
     auto tile_ops = [&](int tile_m, int tile_n) {
         return typename TL::Operands{W, ldw_bytes, static_cast<int64_t>(tile_m) * TL::BM, V, X, ldx_bytes,
                                      static_cast<int64_t>(tile_n) * TL::BN, T_valid, 0, 0};
@@ -444,56 +456,78 @@ recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V,
                 for (int r = 0; r < TL::ACC_R; ++r)
                     if (m0 + TL::acc_row(fm, r) >= V)
 #pragma unroll
-                        for (int fn = 0; fn < TL::FN; ++fn) acc[fm][fn][r] = kNegBig;
+                        for (int fn = 0; fn < TL::FN; ++fn) acc[fm][fn][r] = -INFINITY;
         }
         // A lane holds runs of four consecutive vocabulary entries (8 bytes of bf16) of ONE token,
         // at offset 32 * (fm % 4) + 8 * group inside that token's 128-byte row of a block of dZ.
-        // Transposed across the four lane groups, the lane of group q holds 32 contiguous bytes
-        // (the runs with fm % 4 == q of all four groups): two 16-byte stores per block.
-        // (Everything that depends on the lane is derived here from a value the compiler cannot
-        // trace, so that none of it is kept in registers across the main loop.)
+        // After an exchange between neighbouring lane groups a lane holds 16 contiguous bytes of
+        // two blocks out of four: per store instruction every token gets a contiguous 64-byte half
+        // of its row.  (Everything that depends on the lane is derived here from a value the
+        // compiler cannot trace, so that none of it is kept in registers across the main loop.)
         int lane = threadIdx.x & 63;
         asm volatile("" : "+v"(lane));
         const int grp = lane >> 4, col = lane & 15;
         const int wave_blk = tile_m * (TL::BM / kBlockK) + TL::wave_m0() / kBlockK;
-        const float4 *tok_w = tok + static_cast<int64_t>(n0) + TL::wave_n0();  // records of this wavefront's 64 tokens
+        const int piece = (grp & 1) * 16 + (grp & 2) * 4;  // elements: byte offset 32 * (g & 1) + 8 * (g & 2)
+        // the records of this wavefront's 64 tokens, one per lane (handed round with lane shuffles below)
+        const float4 rec = tok[static_cast<int64_t>(n0) + TL::wave_n0() + lane];
 #pragma unroll
         for (int fn = 0; fn < TL::FN; ++fn) {
-            const float4 tk = tok_w[fn * TL::MI + col];
-            const float gt = tk.x, ngt = -gt, nl = tk.y;
+            const int src = fn * TL::MI + col;
+            const float ag = __shfl(rec.x, src, kWave), nl = __shfl(rec.y, src, kWave);
+            const uint32_t ts = __float_as_uint(__shfl(rec.z, src, kWave));
+            // the values are formed as |g| * p >= 0; the sign of -g is put on afterwards, two at a time
+            const uint32_t sgn = (ts & 0x80000000u) ? 0x80008000u : 0u;
             // where the target's vocabulary row sits among this wave's rows, if it does
-            const int dy = __float_as_int(tk.z) - (m0 + TL::wave_m0());
+            const int dy = static_cast<int>(ts & 0x7fffffffu) - (m0 + TL::wave_m0());
             int fq = 0, rq = 0, gq = 0;
             const bool in_wave = static_cast<unsigned>(dy) < static_cast<unsigned>(TL::WM);
             if (in_wave) TL::locate(dy, fq, rq, gq);
             const bool mine = in_wave && gq == grp;
-            bf16_t *row = dZ + static_cast<int64_t>(n0 + TL::wave_n0() + fn * TL::MI + col) * kBlockK + grp * 16;
+            bf16_t *row = dZ + static_cast<int64_t>(n0 + TL::wave_n0() + fn * TL::MI + col) * kBlockK + piece;
 #pragma unroll
             for (int b = 0; b < TL::FM / 4; ++b) {
                 uint32_t lo[4], hi[4];  // bf16 pairs: lo = rows +0,+1, hi = rows +2,+3 of the run of block 4b+q
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int fm = 4 * b + q;
-                    float dz[4];
+                    float e[4];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) dz[i] = ngt * __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][i], kLog2e, nl));
-                    if (mine && fm == fq) {  // the one-hot term
+                    for (int i = 0; i < 4; ++i) e[i] = __builtin_amdgcn_exp2f(fmaf(acc[4 * b + q][fn][i], kLog2e, nl));
+                    lo[q] = pack_bf16x2_rn(e[0], e[1]);
+                    hi[q] = pack_bf16x2_rn(e[2], e[3]);
+                }
+                if (mine && (fq >> 2) == b) {  // rare: the one-hot term, |g| * (p - 1) before the sign goes on
+                    float x = 0.0f;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
 #pragma unroll
                         for (int i = 0; i < 4; ++i)
-                            if (rq == i) dz[i] += gt;
-                    }
-                    lo[q] = pack_bf16x2_rn(dz[0], dz[1]);
-                    hi[q] = pack_bf16x2_rn(dz[2], dz[3]);
+                            if ((fq & 3) == q && rq == i) x = acc[4 * b + q][fn][i];
+                    const uint32_t v = f32_to_bf16(__builtin_amdgcn_exp2f(fmaf(x, kLog2e, nl)) - ag);
+                    const uint32_t keep = (rq & 1) ? 0x0000ffffu : 0xffff0000u, put = (rq & 1) ? v << 16 : v;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        if ((fq & 3) == q) {
+                            if (rq & 2) hi[q] = (hi[q] & keep) | put;
+                            else lo[q] = (lo[q] & keep) | put;
+                        }
                 }
-                transpose_lane_groups(lo[0], lo[1], lo[2], lo[3]);
-                transpose_lane_groups(hi[0], hi[1], hi[2], hi[3]);
-                uint4 *out = reinterpret_cast<uint4 *>(row + (wave_blk + b) * dz_blk);
-                out[0] = make_uint4(lo[0], hi[0], lo[1], hi[1]);
-                out[1] = make_uint4(lo[2], hi[2], lo[3], hi[3]);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    lo[q] ^= sgn;
+                    hi[q] ^= sgn;
+                }
+                swap_lane_groups(lo[0], lo[1]);
+                swap_lane_groups(hi[0], hi[1]);
+                swap_lane_groups(lo[2], lo[3]);
+                swap_lane_groups(hi[2], hi[3]);
+                bf16_t *out = row + (wave_blk + b) * dz_blk;
+                *reinterpret_cast<uint4 *>(out) = make_uint4(lo[0], hi[0], lo[1], hi[1]);
+                *reinterpret_cast<uint4 *>(out + kBlockK / 2) = make_uint4(lo[2], hi[2], lo[3], hi[3]);
             }
         }
     };
-    for (; item < n_items; item = advance(item + nslot, tm, tn)) {
+    for (int tm = vt0; tm < vt1; ++tm) {
         TL::Acc acc;
         TL::zero(acc);
         TL::mainloop(tile_ops(tm, tn), KT, lds, acc);
@@ -709,8 +743,7 @@ static FwdPlan plan_fwd(const spo_pg_desc *d, void *ws) {
     p.nTt = ceil_div(d->T, TL::BN);
     p.nVt = ceil_div(d->V, TL::BM);
     p.T_pad = p.nTt * TL::BN;
-    int64_t ns = std::max<int64_t>(kSweepSplits, ceil_div(2048, std::max<int64_t>(p.nTt, 1)));
-    p.nsplit = static_cast<int>(std::min<int64_t>(ns, p.nVt));
+    p.nsplit = SweepMap(p.nTt, p.nVt).nsplit;
     p.Kc = d->dtype == SPO_FP32 ? kSplitTerms * d->H : d->H;
     p.nblk_tok = ceil_div(std::max<int64_t>(d->T, 1), kTokThreads);
     Arena a(ws);
@@ -770,9 +803,7 @@ int fused_fwd(const spo_pg_desc *d, float *loss, float *logp, float *lse, float 
                 W = static_cast<const char *>(d->W);
             }
         }
-        // token tiles per XCD, in whole patches of 4 when the splits come in groups of 8
-        const int64_t per_xcd = p.nsplit % 8 == 0 ? round_up(ceil_div(p.nTt, 8), 4) : ceil_div(p.nTt, 8);
-        const int64_t blocks = per_xcd * 8 * p.nsplit;
+        const int64_t blocks = SweepMap(p.nTt, p.nVt).blocks();
         ScopedKernelTimer timer(kTimeFwdSweep, s);
         fwd_sweep_kernel<<<static_cast<unsigned>(blocks), TL::NT, kSweepLds, s>>>(
             W, p.Kc * 2, d->V, X, p.Kc * 2, d->T, static_cast<int>(p.Kc / kBK), p.nsplit, p.nTt, p.nVt, p.T_pad,
@@ -886,10 +917,6 @@ int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float g
     const BwdPlan p = plan_bwd(d, chunk_tokens, ws, need_acc);
     if (ws_bytes < p.bytes) return SPO_EWORKSPACE;
     if ((rc = set_lds_limit())) return rc;
-    int dev = 0, ncu = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || ncu < 1)
-        return SPO_EHIP;
     const int64_t H = d->H, V = d->V, T = d->T;
     float *dW32 = need_acc ? p.dW_acc : static_cast<float *>(d_W);
     if (T == 0) {
@@ -952,10 +979,8 @@ int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float g
             Xk = Xrows = xc;
         }
         {
-            // one persistent workgroup per compute unit (a workgroup fills a unit's LDS), in whole
-            // groups of 8 so that every XCD gets the same number
-            const TileOrder ord(nVt, Tcp / TL::BN);
-            const int64_t wgs = std::min<int64_t>(std::max(ncu / 8, 1) * 8, ord.blocks());
+            const SweepMap map(Tcp / TL::BN, nVt);
+            const int64_t wgs = map.blocks();
             ScopedKernelTimer timer(kTimeRecompute, s);
             recompute_dz_kernel<<<static_cast<unsigned>(wgs), TL::NT, TL::LDS_BYTES, s>>>(
                 reinterpret_cast<const char *>(Wk), p.Kc * 2, V, reinterpret_cast<const char *>(Xk), p.Kc * 2,
