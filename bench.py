@@ -3,7 +3,10 @@
 
 A step is one pass of the whole path over one synthetic batch: prioritized
 sampling -> advantages -> tracker update -> fused LM-head + clipped
-policy-gradient loss forward -> backward (dHidden and dW).  Default workload: the
+policy-gradient loss forward -> backward (dHidden and dW); with --path one_call
+(the default) loss and gradients come from spo_pg_loss_fwd_bwd, which forms the
+logits once, with --path two_calls from spo_pg_loss_fwd followed by
+spo_pg_loss_bwd, which forms them twice.  Default workload: the
 Qwen3-8B head shape (H=4096, V=151936, bf16), 128 packed variable-length
 responses (~280k tokens).  Prints ONE JSON line.
 
@@ -25,6 +28,7 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 MFMA_KERNELS = ("fwd_sweep", "bwd_recompute", "bwd_dhidden", "bwd_dw")
+HBM_KERNELS = ("logits_to_dz",)
 
 
 def log(*a):
@@ -37,11 +41,11 @@ def kernel_source_digest() -> str:
     return source_digest()
 
 
-def profiled_traffic(workload: str, chunk_tokens: int):
-    """Bytes across the L2 <-> fabric boundary per launch (reads + writes) of each MFMA kernel, from the
-    tracked rocprofv3 summary profiles/step_<workload>_hbm_traffic.md, or None when that summary was
-    taken from other kernel sources, another chunk size, or does not exist."""
-    path = os.path.join(ROOT, "profiles", f"step_{workload.lower()}_hbm_traffic.md")
+def profiled_traffic(workload: str, chunk_tokens: int, one_call: bool):
+    """Bytes across the L2 <-> fabric boundary per launch (reads + writes) of each heavy kernel, from the
+    tracked rocprofv3 summary profiles/step_<workload>_[two_calls_]hbm_traffic.md, or None when that
+    summary was taken from other kernel sources, another chunk size, or does not exist."""
+    path = os.path.join(ROOT, "profiles", f"step_{workload.lower()}_{'' if one_call else 'two_calls_'}hbm_traffic.md")
     try:
         text = open(path).read()
     except OSError:
@@ -64,7 +68,7 @@ def cpu_model() -> str:
     return "unknown"
 
 
-def run_workload(spo, wl, torch, name, steps, warmup, chunk_tokens, want_d_hidden):
+def run_workload(spo, wl, torch, name, steps, warmup, chunk_tokens, want_d_hidden, one_call=True):
     """Times `steps` steps of workload `name`; returns (result dict, live tensors for the follow-up legs)."""
     import ctypes as C
     dev = "cuda"
@@ -89,8 +93,12 @@ def run_workload(spo, wl, torch, name, steps, warmup, chunk_tokens, want_d_hidde
     adv_holder = torch.zeros(B, dtype=torch.float32, device=dev)
     desc = spo.make_desc(tb.hidden, tb.W, target, old_logp, mask, adv_holder, cu, cfg.eps_low, cfg.eps_high)
     ws_s = torch.empty(spo.lib().spo_sample_prompts_workspace_bytes(cfg.N, B), dtype=torch.uint8, device=dev)
-    ws_f = torch.empty(max(256, spo.lib().spo_pg_loss_fwd_workspace_bytes(C.byref(desc[0]))), dtype=torch.uint8, device=dev)
-    ws_b = torch.empty(max(256, spo.spo_pg_loss_bwd_workspace_bytes(desc, chunk_tokens)), dtype=torch.uint8, device=dev)
+    if one_call:
+        ws_f = torch.empty(256, dtype=torch.uint8, device=dev)
+        ws_b = torch.empty(max(256, spo.spo_pg_loss_fwd_bwd_workspace_bytes(desc, chunk_tokens)), dtype=torch.uint8, device=dev)
+    else:
+        ws_f = torch.empty(max(256, spo.lib().spo_pg_loss_fwd_workspace_bytes(C.byref(desc[0]))), dtype=torch.uint8, device=dev)
+        ws_b = torch.empty(max(256, spo.spo_pg_loss_bwd_workspace_bytes(desc, chunk_tokens)), dtype=torch.uint8, device=dev)
     d_W = torch.empty((V, H), dtype=torch.float32, device=dev)
     log(f"[bench] workspaces: fwd {ws_f.numel() / 2**30:.2f} GiB, bwd {ws_b.numel() / 2**30:.2f} GiB")
     state = {}
@@ -100,9 +108,13 @@ def run_workload(spo, wl, torch, name, steps, warmup, chunk_tokens, want_d_hidde
         _, adv, _ = spo.spo_advantages(alpha, beta, idx, reward)
         spo.spo_tracker_update(alpha, beta, idx, reward, kl, cfg.d_half, cfg.rho_min, cfg.rho_max)
         adv_holder.copy_(adv)   # the descriptor points at adv_holder
-        loss, logp, lse, stats = spo.spo_pg_loss_fwd(desc, workspace=ws_f)
-        spo.spo_pg_loss_bwd(desc, logp, lse, 1.0, d_W=d_W, want_d_hidden=want_d_hidden, chunk_tokens=chunk_tokens,
-                            workspace=ws_b)
+        if one_call:
+            loss, logp, lse, stats, _, _ = spo.spo_pg_loss_fwd_bwd(desc, 1.0, d_W=d_W, want_d_hidden=want_d_hidden,
+                                                                   chunk_tokens=chunk_tokens, workspace=ws_b)
+        else:
+            loss, logp, lse, stats = spo.spo_pg_loss_fwd(desc, workspace=ws_f)
+            spo.spo_pg_loss_bwd(desc, logp, lse, 1.0, d_W=d_W, want_d_hidden=want_d_hidden, chunk_tokens=chunk_tokens,
+                                workspace=ws_b)
         state["loss"], state["stats"] = loss, stats
 
     for w in range(warmup):
@@ -142,7 +154,15 @@ def run_workload(spo, wl, torch, name, steps, warmup, chunk_tokens, want_d_hidde
                        "avg_launch_ms": round(ms / n, 4), "tflops": round(thv[k] / (ms / steps * 1e-3) / 1e12, 1)}
     executed = sum(thv[k] for k in kern)
     useful = sum(thv[k] for k in kern if k != "bwd_recompute")
+    # the pass from stored logits to logit gradients (one-call path): 2 V bytes read and 2 V written per active token
+    V_blk = (V + 255) // 256 * 256
+    for k in HBM_KERNELS:
+        ms, n = times[k]
+        if n:
+            kern[k] = {"ms_per_step": round(ms / steps, 3), "launches_per_step": n // steps, "avg_launch_ms": round(ms / n, 4),
+                       "GBps": round(4.0 * t_active * V_blk / (ms / steps * 1e-3) / 1e9, 1), "bound": "hbm"}
     res = {
+        "path": "one_call (spo_pg_loss_fwd_bwd)" if one_call else "two_calls (spo_pg_loss_fwd, spo_pg_loss_bwd)",
         "tokens_per_s": round(T / sec, 1), "ms_per_step": round(sec * 1e3, 3),
         "ms_per_step_median": round(step_ms[len(step_ms) // 2], 3), "ms_per_step_min": round(step_ms[0], 3),
         "T": T, "B": B, "H": H, "V": V, "N": cfg.N, "active_tokens": t_active, "clipped_share": round(stats[1], 5),
@@ -166,6 +186,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="C3", choices=["C2", "C3", "C4"])
     ap.add_argument("--chunk-tokens", type=int, default=0, help="backward chunk (0: the library's bounded default)")
+    ap.add_argument("--path", default="one_call", choices=["one_call", "two_calls"],
+                    help="loss and gradients from one call (logits formed once) or from forward then backward")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-logits-in", action="store_true")
     ap.add_argument("--no-small", action="store_true", help="skip the tracker / advantage / sampler timings")
@@ -201,17 +223,18 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    res, live = run_workload(spo, wl, torch, args.workload, args.steps, args.warmup, args.chunk_tokens, True)
+    one_call = args.path == "one_call"
+    res, live = run_workload(spo, wl, torch, args.workload, args.steps, args.warmup, args.chunk_tokens, True, one_call)
     cfg, tb, times, thv = live["cfg"], live["tb"], live["times"], live["thv"]
     T, H, V, B = res["T"], res["H"], res["V"], res["B"]
     kern = res["kernels"]
 
     # ---------------------------------------------------------------- roofline of the dominant kernel
-    dom = max(kern, key=lambda k: kern[k]["ms_per_step"])
+    dom = max((k for k in kern if k in MFMA_KERNELS), key=lambda k: kern[k]["ms_per_step"])
     ms_dom, n_dom = times[dom]
     flops_per_launch = thv[dom] * args.steps / n_dom
     achieved = flops_per_launch / (ms_dom / n_dom * 1e-3) / 1e12
-    traffic = profiled_traffic(cfg.name, args.chunk_tokens)
+    traffic = profiled_traffic(cfg.name, args.chunk_tokens, one_call)
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                 "traffic": None if traffic is None else traffic.get(dom),
@@ -225,7 +248,8 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": res["workload"], "T": T, "B": B, "H": H, "V": V, "N": cfg.N,
                    "eps": [cfg.eps_low, cfg.eps_high], "d_half": cfg.d_half,
-                   "chunk_tokens": args.chunk_tokens or "library default (logit gradients of a chunk <= 8 GiB)",
+                   "path": res["path"],
+                   "chunk_tokens": args.chunk_tokens or "library default (a piece's stored logits and logit gradients <= 8 GiB)",
                    "workspace_bytes": res["workspace_bytes"]},
         "active_tokens": res["active_tokens"], "tflops_useful": res["tflops_useful"],
         "tflops_executed": res["tflops_executed"], "mfma_util_executed": res["mfma_util_executed"],
@@ -373,7 +397,7 @@ def main() -> int:
         for name, (st, wu) in {"C2": (20, 3), "C4": (2, 1)}.items():
             if name == args.workload:
                 continue
-            r, lv = run_workload(spo, wl, torch, name, st, wu, args.chunk_tokens, True)
+            r, lv = run_workload(spo, wl, torch, name, st, wu, args.chunk_tokens, True, one_call)
             del lv
             torch.cuda.empty_cache()
             r["steps"], r["warmup"] = st, wu

@@ -287,6 +287,35 @@ int spo_pg_loss_bwd(const spo_pg_desc *d, const float *logp, const float *lse, f
                     int accumulate_dW, void *d_logits, int64_t chunk_tokens, void *ws,
                     size_t ws_bytes, spo_stream_t stream);
 
+/* Forward and backward in one call (fused form only), for callers that know
+ * grad_loss = d(total)/d(loss) before the forward: a loss that enters the total with
+ * a fixed weight, which is how the policy-gradient objective is used (Method, the
+ * PPO-Clip objective is the whole training loss).  Same results as spo_pg_loss_fwd
+ * followed by spo_pg_loss_bwd, up to the rounding of the stored logits (below), at
+ * three contractions of size T x V x H instead of four: the logits are not formed
+ * a second time.
+ * The batch is walked in pieces of chunk_tokens tokens (rounded up to a multiple of
+ * 256).  The forward sweep of a piece also stores its logits in the workspace: 2 * V
+ * bytes per token, as fp16 of the logit minus an offset per (token, 128 vocabulary
+ * entries): the largest logit the sweep has met for that token up to there.  An
+ * entry within d of its row's largest logit is thus stored within d of zero, where
+ * fp16 resolves d * 2^-11: the entries that carry the softmax are the most exact,
+ * and the error this adds to a probability p is at most p * ln(1/p) * 2^-11.  (A
+ * logit more than 65504 below its offset is stored as -inf: probability zero.)
+ * The piece's log-probs then give the gradient factors, one pass turns the stored logits of
+ * the tokens with a non-zero factor into bf16 logit gradients, and the two
+ * contractions follow as in spo_pg_loss_bwd.  chunk_tokens = 0 lets the library
+ * choose: the most tokens, in multiples of 4096, whose stored logits stay within
+ * 8 GiB (24576 at V = 151936); their logit gradients take as much again.  Shorter
+ * pieces cost more passes over d_W.
+ * Arguments as in spo_pg_loss_fwd and spo_pg_loss_bwd; d_hidden and d_W may each be
+ * NULL.  Errors as there; a desc with logits != NULL -> SPO_EUNSUPPORTED. */
+size_t spo_pg_loss_fwd_bwd_workspace_bytes(const spo_pg_desc *d, int64_t chunk_tokens);
+int spo_pg_loss_fwd_bwd(const spo_pg_desc *d, float grad_loss, float *loss, float *logp,
+                        float *lse, float *stats, void *d_hidden, int d_hidden_dtype,
+                        void *d_W, int d_W_dtype, int accumulate_dW, int64_t chunk_tokens,
+                        void *ws, size_t ws_bytes, spo_stream_t stream);
+
 /* ---------------------------------------------------------------------------
  * Per-kernel timing (measurement aid, not part of the method; the only state
  * the library keeps).  While enabled, the loss entry points bracket each launch
@@ -295,9 +324,10 @@ int spo_pg_loss_bwd(const spo_pg_desc *d, const float *logp, const float *lse, f
  * milliseconds and the number of launches per kernel class, and forgets them.
  * Classes: 0 fused forward vocabulary sweep, 1 backward logits recompute,
  * 2 backward dHidden contraction, 3 backward dW contraction, 4 logits-in forward
- * pass, 5 logits-in backward pass.  ms and launches are HOST arrays of 6.
+ * pass, 5 logits-in backward pass, 6 stored logits -> logit gradients (one-call
+ * forward + backward).  ms and launches are HOST arrays of 7.
  * ------------------------------------------------------------------------- */
-#define SPO_TIMING_CLASSES 6
+#define SPO_TIMING_CLASSES 7
 int spo_kernel_timing_enable(int enable);
 int spo_kernel_timing_read(float *ms, int32_t *launches);
 

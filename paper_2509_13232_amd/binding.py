@@ -26,9 +26,10 @@ EXPORTS = (
     "spo_tracker_init",
     "spo_pg_loss_fwd_workspace_bytes", "spo_pg_loss_fwd",
     "spo_pg_loss_bwd_workspace_bytes", "spo_pg_loss_bwd",
+    "spo_pg_loss_fwd_bwd_workspace_bytes", "spo_pg_loss_fwd_bwd",
     "spo_kernel_timing_enable", "spo_kernel_timing_read",
 )
-TIMING_CLASSES = ("fwd_sweep", "bwd_recompute", "bwd_dhidden", "bwd_dw", "logits_fwd", "logits_bwd")
+TIMING_CLASSES = ("fwd_sweep", "bwd_recompute", "bwd_dhidden", "bwd_dw", "logits_fwd", "logits_bwd", "logits_to_dz")
 
 
 class SpoError(RuntimeError):
@@ -91,6 +92,11 @@ def lib():
         L.spo_pg_loss_bwd.restype = C.c_int
         L.spo_pg_loss_bwd.argtypes = [C.POINTER(PgDesc), vp, vp, f32, vp, C.c_int, vp, C.c_int, C.c_int,
                                       vp, i64, vp, sz, vp]
+        L.spo_pg_loss_fwd_bwd_workspace_bytes.restype = sz
+        L.spo_pg_loss_fwd_bwd_workspace_bytes.argtypes = [C.POINTER(PgDesc), i64]
+        L.spo_pg_loss_fwd_bwd.restype = C.c_int
+        L.spo_pg_loss_fwd_bwd.argtypes = [C.POINTER(PgDesc), f32, vp, vp, vp, vp, vp, C.c_int, vp, C.c_int, C.c_int,
+                                          i64, vp, sz, vp]
         L.spo_kernel_timing_enable.restype = C.c_int
         L.spo_kernel_timing_enable.argtypes = [C.c_int]
         L.spo_kernel_timing_read.restype = C.c_int
@@ -352,3 +358,36 @@ def spo_pg_loss_bwd(desc, logp, lse, grad_loss=1.0, d_hidden_dtype=None, d_W_dty
                                  _dt(d_W.dtype) if d_W is not None else 0, int(bool(accumulate_dW)), None,
                                  int(chunk_tokens), _ptr(ws), ws.numel(), _stream()), "spo_pg_loss_bwd")
     return dx, d_W
+
+
+def spo_pg_loss_fwd_bwd_workspace_bytes(desc, chunk_tokens=0) -> int:
+    return int(lib().spo_pg_loss_fwd_bwd_workspace_bytes(C.byref(desc[0]), int(chunk_tokens)))
+
+
+def spo_pg_loss_fwd_bwd(desc, grad_loss=1.0, d_hidden_dtype=None, d_W_dtype=torch.float32, d_W=None,
+                        accumulate_dW=False, want_d_hidden=True, want_d_W=True, chunk_tokens=0, workspace=None,
+                        want_stats=True):
+    """Fused form only.  Returns (loss[1], logp[T], lse[T], stats[4] or None, d_hidden or None, d_W or None)."""
+    d, keep = desc
+    dev = keep[3].device
+    hidden, W = keep[0], keep[1]
+    loss = torch.empty(1, dtype=torch.float32, device=dev)
+    logp = torch.empty(max(d.T, 1), dtype=torch.float32, device=dev)[:d.T]
+    lse = torch.empty(max(d.T, 1), dtype=torch.float32, device=dev)[:d.T]
+    stats = torch.empty(4, dtype=torch.float32, device=dev) if want_stats else None
+    nbytes = lib().spo_pg_loss_fwd_bwd_workspace_bytes(C.byref(d), int(chunk_tokens))
+    ws = _workspace(nbytes, dev, workspace)
+    dx = None
+    if want_d_hidden:
+        dx = torch.empty((d.T, d.H), dtype=d_hidden_dtype or hidden.dtype, device=dev)
+    if want_d_W and d_W is None:
+        if accumulate_dW:
+            raise ValueError("accumulate_dW needs an existing d_W")
+        d_W = torch.empty(W.shape, dtype=d_W_dtype, device=dev)
+    if not want_d_W:
+        d_W = None
+    _check(lib().spo_pg_loss_fwd_bwd(C.byref(d), float(grad_loss), _ptr(loss), _ptr(logp), _ptr(lse), _ptr(stats),
+                                     _ptr(dx), _dt(dx.dtype) if dx is not None else 0, _ptr(d_W),
+                                     _dt(d_W.dtype) if d_W is not None else 0, int(bool(accumulate_dW)),
+                                     int(chunk_tokens), _ptr(ws), ws.numel(), _stream()), "spo_pg_loss_fwd_bwd")
+    return loss, logp, lse, stats, dx, d_W

@@ -35,14 +35,15 @@ struct FwdPartial {
 
 // One thread per token: merges the per-split (running max, sum of exponentials)
 // pairs into lse, forms logp and the surrogate, and reduces this block's masked
-// sums.  z_target[t] is the logit of the sampled token.
+// sums.  z_target[t] is the logit of the sampled token.  The per-token arrays start at token
+// t_base of the batch (a multiple of the block size; 0 unless the batch is walked in pieces).
 static __global__ void __launch_bounds__(kTokThreads)
 token_loss_kernel(const float *__restrict__ part_max, const float *__restrict__ part_sum, int nsplit,
                   int64_t split_stride, const float *__restrict__ z_target, int64_t T,
                   const float *__restrict__ old_logp, const uint8_t *__restrict__ mask,
                   const float *__restrict__ adv_norm, const int32_t *__restrict__ cu, int B, float eps_low,
                   float eps_high, float *__restrict__ logp_out, float *__restrict__ lse_out,
-                  FwdPartial *__restrict__ partials) {
+                  FwdPartial *__restrict__ partials, int64_t t_base = 0) {
     __shared__ double scratch[kTokThreads / kWave];
     const int64_t t = static_cast<int64_t>(blockIdx.x) * kTokThreads + threadIdx.x;
     double so = 0.0, cnt = 0.0, clp = 0.0, sr = 0.0;
@@ -56,7 +57,7 @@ token_loss_kernel(const float *__restrict__ part_max, const float *__restrict__ 
         lse_out[t] = lse;
         logp_out[t] = logp;
         if (!mask || mask[t]) {
-            const float adv = adv_norm[response_of_token(cu, B, t)];
+            const float adv = adv_norm[response_of_token(cu, B, t_base + t)];
             const Surrogate r = surrogate(logp, old_logp[t], adv, eps_low, eps_high);
             so = logp == logp ? r.obj : logp;  // a NaN log-prob (target id outside the vocabulary) reaches the loss
             cnt = 1.0;
@@ -111,18 +112,18 @@ mask_count_kernel(const uint8_t *__restrict__ mask, int64_t T, double *__restric
 }
 
 // g[t] = -(mask_t / M) * A * ratio_t * [unclipped branch is the minimum] * grad_loss;
-// entries T <= t < T_pad are zero so that padded tokens contribute nothing.
+// entries T <= t < T_pad are zero so that padded tokens contribute nothing.  t_base as above.
 static __global__ void __launch_bounds__(kTokThreads)
 grad_scale_kernel(const float *__restrict__ logp, const float *__restrict__ old_logp,
                   const uint8_t *__restrict__ mask, const float *__restrict__ adv_norm,
                   const int32_t *__restrict__ cu, int B, int64_t T, int64_t T_pad, float eps_low, float eps_high,
-                  float grad_loss, const double *__restrict__ count, float *__restrict__ g) {
+                  float grad_loss, const double *__restrict__ count, float *__restrict__ g, int64_t t_base = 0) {
     const int64_t t = static_cast<int64_t>(blockIdx.x) * kTokThreads + threadIdx.x;
     if (t >= T_pad) return;
     float out = 0.0f;
     const double M = count[0];
     if (t < T && M > 0.0 && (!mask || mask[t])) {
-        const float adv = adv_norm[response_of_token(cu, B, t)];
+        const float adv = adv_norm[response_of_token(cu, B, t_base + t)];
         const Surrogate r = surrogate(logp[t], old_logp[t], adv, eps_low, eps_high);
         if (r.active) out = -(adv * r.ratio * grad_loss) / static_cast<float>(M);
     }

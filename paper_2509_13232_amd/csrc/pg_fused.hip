@@ -269,9 +269,12 @@ target_logit_kernel(const T_ *__restrict__ X, const T_ *__restrict__ Wvh, int64_
 struct SweepMap {
     int nsplit;
     int64_t nTt, nVt, per_xcd;
-    __host__ __device__ SweepMap(int64_t token_tiles, int64_t vocab_tiles) : nTt(token_tiles), nVt(vocab_tiles) {
+    // splits = 0: chosen here; otherwise the caller's number (kept when it is a multiple of 8 or below 8)
+    __host__ __device__ SweepMap(int64_t token_tiles, int64_t vocab_tiles, int splits = 0)
+        : nTt(token_tiles), nVt(vocab_tiles) {
         int64_t ns = (2048 + (nTt > 0 ? nTt : 1) - 1) / (nTt > 0 ? nTt : 1);  // small batches: more splits fill the chip
         ns = ns < kSweepSplits ? kSweepSplits : ns;
+        if (splits > 0) ns = splits;
         ns = ns < nVt ? ns : nVt;
         nsplit = static_cast<int>(ns >= 8 ? ns / 8 * 8 : ns);  // whole groups of 8 splits whenever there are 8
         const int64_t x = (nTt + 7) / 8;
@@ -292,17 +295,47 @@ struct SweepMap {
         }
         return jt < nTt;
     }
-    __device__ int64_t first_tile(int split) const { return split * nVt / nsplit; }
+    __host__ __device__ int64_t first_tile(int split) const { return split * nVt / nsplit; }
 };
 
 constexpr int kSweepLds = TL::LDS_BYTES + TL::NT * 32;  // operand stages + the per-thread running state
 
+// Exchange between neighbouring groups of 16 lanes: v_permlane16_swap(a, b) swaps the odd groups
+// of a with the even groups of b.  With a, b the values a lane holds for two consecutive MFMA
+// blocks q, q+1, lane group g ends up with (in a, b) the values of block q + (g & 1) from lane
+// groups (g & 2) and (g & 2) + 1.
+__device__ __forceinline__ void swap_lane_groups(uint32_t &a, uint32_t &b) {
+    typedef unsigned v2u __attribute__((ext_vector_type(2)));
+    const v2u t = __builtin_amdgcn_permlane16_swap(a, b, false, false);
+    a = t.x;
+    b = t.y;
+}
+
+// two floats as a pair of IEEE halves, round to nearest even
+__device__ __forceinline__ uint32_t pack_f16x2_rn(float lo, float hi) {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    const h2 v = {static_cast<_Float16>(lo), static_cast<_Float16>(hi)};
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+// Emit = false: the forward proper; the logits exist in registers only.
+// Emit = true (the one-call forward + backward): every finished tile is also written out, as
+// fp16 of (logit - offset), in the blocked layout of the logit gradients: the logit of token n
+// (row of this launch), vocabulary entry v at Z + (v / 64) * z_blk + n * 64 + v % 64.  The
+// offset is the running maximum of the token over the 128 vocabulary rows per tile that the
+// wavefront has seen so far in its sweep, this tile included: one value per (vocabulary tile,
+// half of the tile, token), written to offs[(tile * 2 + half) * T_pad + n].  Stored values are
+// <= 0, and an entry within d of the row's largest logit is stored within d of zero, where
+// fp16 resolves 2^-11 * d: the entries that carry the softmax are the most exact ones.  Rows
+// past the vocabulary are stored as -inf.
+template <bool Emit>
 __global__ void __launch_bounds__(TL::NT)
 fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const char *__restrict__ X,
                  int64_t ldx_bytes, int64_t T, int KT, int nsplit, int64_t nTt, int64_t nVt, int64_t T_pad,
-                 float *__restrict__ part_max, float *__restrict__ part_sum) {
+                 float *__restrict__ part_max, float *__restrict__ part_sum, uint16_t *__restrict__ Z, int64_t z_blk,
+                 float *__restrict__ offs) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    const SweepMap map(nTt, nVt);  // map.nsplit == nsplit: the host sized the partial results with the same map
+    const SweepMap map(nTt, nVt, nsplit);  // the host sized the partial results with the same map
     int split;
     int64_t jt;
     if (!map.tile(blockIdx.x, split, jt)) return;
@@ -357,12 +390,53 @@ fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const
         st[0] = make_float4(m_run[0], m_run[1], m_run[2], m_run[3]);
         st[1] = make_float4(s_run[0], s_run[1], s_run[2], s_run[3]);
     };
+    // Emit: the finished tile (rows past the vocabulary already -inf) as fp16 offsets.  A lane
+    // holds runs of four consecutive vocabulary entries of one token; after an exchange between
+    // neighbouring lane groups it holds 16 contiguous bytes of two 64-entry blocks out of four
+    // (the scheme of the recompute's epilogue below).
+    auto emit = [&](TL::Acc &acc, int64_t vt) {
+        int l = threadIdx.x & 63;
+        asm volatile("" : "+v"(l));  // not to be traced: nothing derived from it lives through the main loop
+        const int grp = l >> 4, col = l & 15;
+        const float4 m4 = state()[0];  // this lane's running maxima, the finished tile included
+        float off[TL::FN] = {m4.x, m4.y, m4.z, m4.w};
+#pragma unroll
+        for (int fn = 0; fn < TL::FN; ++fn) {  // over the four lane groups: all 128 rows of the wavefront
+            off[fn] = fmaxf(off[fn], __shfl_xor(off[fn], 16, kWave));
+            off[fn] = fmaxf(off[fn], __shfl_xor(off[fn], 32, kWave));
+            if (grp == 0)
+                offs[(vt * TL::WGM + TL::wave_m0() / TL::WM) * T_pad + n0 + TL::wave_n0() + fn * TL::MI + col] = off[fn];
+        }
+        const int64_t wave_blk = vt * (TL::BM / kBlockK) + TL::wave_m0() / kBlockK;
+        const int piece = (grp & 1) * 16 + (grp & 2) * 4;  // elements: byte offset 32 * (g & 1) + 8 * (g & 2)
+#pragma unroll
+        for (int fn = 0; fn < TL::FN; ++fn) {
+            uint16_t *row = Z + (n0 + TL::wave_n0() + fn * TL::MI + col) * kBlockK + piece;
+#pragma unroll
+            for (int b = 0; b < TL::FM / 4; ++b) {
+                uint32_t lo[4], hi[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    lo[q] = pack_f16x2_rn(acc[4 * b + q][fn][0] - off[fn], acc[4 * b + q][fn][1] - off[fn]);
+                    hi[q] = pack_f16x2_rn(acc[4 * b + q][fn][2] - off[fn], acc[4 * b + q][fn][3] - off[fn]);
+                }
+                swap_lane_groups(lo[0], lo[1]);
+                swap_lane_groups(hi[0], hi[1]);
+                swap_lane_groups(lo[2], lo[3]);
+                swap_lane_groups(hi[2], hi[3]);
+                uint16_t *out = row + (wave_blk + b) * z_blk;
+                *reinterpret_cast<uint4 *>(out) = make_uint4(lo[0], hi[0], lo[1], hi[1]);
+                *reinterpret_cast<uint4 *>(out + kBlockK / 2) = make_uint4(lo[2], hi[2], lo[3], hi[3]);
+            }
+        }
+    };
     auto tile_ops = [&](int64_t vt) { return typename TL::Operands{W, ldw_bytes, vt * TL::BM, V, X, ldx_bytes, n0, T, 0, 0}; };
     for (int64_t vt = vt0; vt < vt1; ++vt) {
         TL::Acc acc;
         TL::zero(acc);
         TL::mainloop(tile_ops(vt), KT, lds, acc);
         reduce(acc, vt * TL::BM);
+        if (Emit) emit(acc, vt);
     }
     // merge the lane groups that hold different rows of the same token, then the WGM
     // wavefronts that share a token column
@@ -415,17 +489,6 @@ fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const
 //
 // Workgroups map to (token tile, vocabulary split) as in the forward sweep (SweepMap).  The
 // gradients go from the accumulators to memory without a detour through LDS.
-
-// Exchange between neighbouring groups of 16 lanes: v_permlane16_swap(a, b) swaps the odd groups
-// of a with the even groups of b.  With a, b the values a lane holds for two consecutive MFMA
-// blocks q, q+1, lane group g ends up with (in a, b) the values of block q + (g & 1) from lane
-// groups (g & 2) and (g & 2) + 1.
-__device__ __forceinline__ void swap_lane_groups(uint32_t &a, uint32_t &b) {
-    typedef unsigned v2u __attribute__((ext_vector_type(2)));
-    const v2u t = __builtin_amdgcn_permlane16_swap(a, b, false, false);
-    a = t.x;
-    b = t.y;
-}
 
 __global__ void __launch_bounds__(TL::NT)
 recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V,
@@ -624,9 +687,25 @@ gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, cons
     // whole groups of four columns can move as 16 (fp32) or 8 (bf16) bytes when the rows allow it
     const bool vec = ldo % 4 == 0 && N % 4 == 0 && reinterpret_cast<uintptr_t>(out) % 16 == 0;
     constexpr int HALF = TL::BM / 2, ROWS = HALF / TL::NWAVE;
+    // adding to fp32 rows: the old values of a wavefront's rows are all requested before the half
+    // tile is staged, so that their latency passes once per half tile and behind the staging
+    const bool rmw = accumulate && out_dtype == SPO_FP32 && vec;
+    const int64_t n = n0 + 4 * lane;  // this lane's four columns
     __syncthreads();  // the operand stages are no longer read
 #pragma unroll 1
     for (int half = 0; half < 2; ++half) {
+        const int64_t m_first = m0 + half * HALF + TL::wave_id() * ROWS;  // this wavefront's rows of the half tile
+        float4 old[ROWS];
+        if (rmw) {
+#pragma unroll
+            for (int i = 0; i < ROWS; ++i) {
+                old[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                if (m_first + i < m_end && n < N) {
+                    const int64_t m = row_map ? row_map[m_first + i] : m_first + i;
+                    old[i] = *reinterpret_cast<const float4 *>(static_cast<const float *>(out) + m * ldo + n);
+                }
+            }
+        }
         if (TL::wave_m0() == half * HALF) {
 #pragma unroll
             for (int fm = 0; fm < TL::FM; ++fm)
@@ -640,40 +719,47 @@ gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, cons
                     }
         }
         __syncthreads();
-        const int64_t n = n0 + 4 * lane;  // this lane's four columns
+        if (rmw) {
+#pragma unroll
+            for (int i = 0; i < ROWS; ++i) {
+                const int row = TL::wave_id() * ROWS + i;
+                if (m_first + i >= m_end || n >= N) continue;
+                const int64_t m = row_map ? row_map[m_first + i] : m_first + i;
+                const float4 v = *reinterpret_cast<const float4 *>(lds + row * (TL::BN * 4) +
+                                                                   (((lane >> 2) ^ ((row >> 2) & 3)) << 6) + (lane & 3) * 16);
+                *reinterpret_cast<float4 *>(static_cast<float *>(out) + m * ldo + n) =
+                    make_float4(old[i].x + v.x, old[i].y + v.y, old[i].z + v.z, old[i].w + v.w);
+            }
+        } else {
 #pragma unroll 4
-        for (int i = 0; i < ROWS; ++i) {
-            const int row = TL::wave_id() * ROWS + i;
-            int64_t m = m0 + half * HALF + row;
-            if (m >= m_end) break;  // rows are in order: nothing further down either
-            if (row_map) m = row_map[m];
-            const float4 v = *reinterpret_cast<const float4 *>(lds + row * (TL::BN * 4) + (((lane >> 2) ^ ((row >> 2) & 3)) << 6) +
-                                                               (lane & 3) * 16);
-            if (n >= N) continue;
-            if (out_dtype == SPO_FP32) {
-                float *o = static_cast<float *>(out) + m * ldo + n;
-                if (vec) {
-                    float4 w = v;
-                    if (accumulate) {
-                        const float4 old = *reinterpret_cast<const float4 *>(o);
-                        w = make_float4(old.x + v.x, old.y + v.y, old.z + v.z, old.w + v.w);
+            for (int i = 0; i < ROWS; ++i) {
+                const int row = TL::wave_id() * ROWS + i;
+                int64_t m = m_first + i;
+                if (m >= m_end) break;  // rows are in order: nothing further down either
+                if (row_map) m = row_map[m];
+                const float4 v = *reinterpret_cast<const float4 *>(lds + row * (TL::BN * 4) +
+                                                                   (((lane >> 2) ^ ((row >> 2) & 3)) << 6) + (lane & 3) * 16);
+                if (n >= N) continue;
+                if (out_dtype == SPO_FP32) {
+                    float *o = static_cast<float *>(out) + m * ldo + n;
+                    if (vec) {
+                        *reinterpret_cast<float4 *>(o) = v;
+                    } else {
+                        const float e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if (n + j < N) o[j] = accumulate ? o[j] + e[j] : e[j];
                     }
-                    *reinterpret_cast<float4 *>(o) = w;
                 } else {
-                    const float e[4] = {v.x, v.y, v.z, v.w};
+                    bf16_t *o = static_cast<bf16_t *>(out) + m * ldo + n;
+                    if (vec) {
+                        *reinterpret_cast<uint2 *>(o) = make_uint2(pack_bf16x2_rn(v.x, v.y), pack_bf16x2_rn(v.z, v.w));
+                    } else {
+                        const float e[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        if (n + j < N) o[j] = accumulate ? o[j] + e[j] : e[j];
-                }
-            } else {
-                bf16_t *o = static_cast<bf16_t *>(out) + m * ldo + n;
-                if (vec) {
-                    *reinterpret_cast<uint2 *>(o) = make_uint2(pack_bf16x2_rn(v.x, v.y), pack_bf16x2_rn(v.z, v.w));
-                } else {
-                    const float e[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        if (n + j < N) o[j] = f32_to_bf16(e[j]);
+                        for (int j = 0; j < 4; ++j)
+                            if (n + j < N) o[j] = f32_to_bf16(e[j]);
+                    }
                 }
             }
         }
@@ -705,6 +791,62 @@ reduce_split_kernel(const float *__restrict__ partials, int nsplit, int64_t M, i
 }
 
 // ----------------------------------------------------------------------------
+// one-call forward + backward: logit gradients from the logits the forward stored
+// ----------------------------------------------------------------------------
+// dZ[j][v] = g * ([v == target] - exp(z[v] - lse)) for the active tokens j of a piece of the
+// batch, from the fp16 offsets written by fwd_sweep_kernel<true> (z = stored value + offset of
+// the entry's half tile), into the blocked bf16 layout the two contractions read.
+// Row j of the output is token act_idx[j] of the piece; tok[j] is its record (see
+// gather_chunk_kernel); rows from the number of active tokens up to the next multiple of 256
+// are written as zeros, rows beyond are left alone (no contraction reads them).  A wavefront
+// moves 8 rows x 128 bytes of one 64-entry block per step (16 bytes per lane), a workgroup 32
+// rows, over `per_wg` consecutive blocks.
+__global__ void __launch_bounds__(256)
+dz_from_logits_kernel(const uint16_t *__restrict__ Z, int64_t z_blk, const float *__restrict__ offs, int64_t off_stride,
+                      const int32_t *__restrict__ act_idx,
+                      const int32_t *__restrict__ n_act, int64_t rows_cap, const float4 *__restrict__ tok,
+                      bf16_t *__restrict__ dZ, int64_t dz_blk, int64_t n_blk, int per_wg) {
+    const int64_t act = active_rows(n_act, 0, rows_cap);
+    const int64_t j = static_cast<int64_t>(blockIdx.x) * 32 + (threadIdx.x >> 3);
+    if (static_cast<int64_t>(blockIdx.x) * 32 >= (act + TL::BN - 1) / TL::BN * TL::BN) return;
+    const int part = threadIdx.x & 7;  // which 8 of the block's 64 entries
+    const bool live = j < act;
+    const int64_t src = live ? act_idx[j] : 0;
+    const float4 rec = live ? tok[j] : make_float4(0.0f, -INFINITY, __uint_as_float(0x7fffffffu), 0.0f);
+    const uint32_t ts = __float_as_uint(rec.z);
+    const uint32_t sgn = (ts & 0x80000000u) ? 0x80008000u : 0u;  // the values are formed as |g| * p; the sign of -g goes on in pairs
+    const int64_t y = ts & 0x7fffffffu;
+    constexpr int bph = TL::WM / kBlockK;  // blocks per wavefront's half of a tile: one offset each
+    const int64_t b0 = static_cast<int64_t>(blockIdx.y) * per_wg;
+    for (int64_t b = b0; b < b0 + per_wg && b < n_blk; ++b) {
+        uint4 o = make_uint4(0u, 0u, 0u, 0u);
+        if (live) {
+            const float off = offs[(b / bph) * off_stride + src];
+            const float c = fmaf(off, kLog2e, rec.y);  // log2|g| + (offset - lse) * log2(e)
+            const uint4 zz = *reinterpret_cast<const uint4 *>(Z + b * z_blk + src * kBlockK + part * 8);
+            const uint32_t w[4] = {zz.x, zz.y, zz.z, zz.w};
+            float e[8];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+                const h2 h = __builtin_bit_cast(h2, w[i]);
+                e[2 * i] = __builtin_amdgcn_exp2f(fmaf(static_cast<float>(h.x), kLog2e, c));
+                e[2 * i + 1] = __builtin_amdgcn_exp2f(fmaf(static_cast<float>(h.y), kLog2e, c));
+            }
+            const int64_t dy = y - (b * kBlockK + part * 8);
+            if (dy >= 0 && dy < 8) {  // the one-hot term: |g| * (p - 1) before the sign goes on
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (dy == i) e[i] -= rec.x;
+            }
+            o = make_uint4(pack_bf16x2_rn(e[0], e[1]) ^ sgn, pack_bf16x2_rn(e[2], e[3]) ^ sgn,
+                           pack_bf16x2_rn(e[4], e[5]) ^ sgn, pack_bf16x2_rn(e[6], e[7]) ^ sgn);
+        }
+        *reinterpret_cast<uint4 *>(dZ + b * dz_blk + j * kBlockK + part * 8) = o;
+    }
+}
+
+// ----------------------------------------------------------------------------
 // host side
 // ----------------------------------------------------------------------------
 // The kernels use more dynamic LDS than the default limit allows.  The attribute belongs
@@ -712,7 +854,9 @@ reduce_split_kernel(const float *__restrict__ partials, int nsplit, int64_t M, i
 // table lookup) rather than remembered in a process-wide flag.
 static int set_lds_limit() {
     hipError_t e = hipSuccess;
-    e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_sweep_kernel),
+    e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_sweep_kernel<false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kSweepLds);
+    e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_sweep_kernel<true>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kSweepLds);
     e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(recompute_dz_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
@@ -805,9 +949,9 @@ int fused_fwd(const spo_pg_desc *d, float *loss, float *logp, float *lse, float 
         }
         const int64_t blocks = SweepMap(p.nTt, p.nVt).blocks();
         ScopedKernelTimer timer(kTimeFwdSweep, s);
-        fwd_sweep_kernel<<<static_cast<unsigned>(blocks), TL::NT, kSweepLds, s>>>(
+        fwd_sweep_kernel<false><<<static_cast<unsigned>(blocks), TL::NT, kSweepLds, s>>>(
             W, p.Kc * 2, d->V, X, p.Kc * 2, d->T, static_cast<int>(p.Kc / kBK), p.nsplit, p.nTt, p.nVt, p.T_pad,
-            p.part_max, p.part_sum);
+            p.part_max, p.part_sum, nullptr, 0, nullptr);
     }
     if (d->T > 0) {
         if (d->dtype == SPO_FP32)
@@ -1004,6 +1148,217 @@ int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float g
                                   0, Tcp * kBlockK, s);
         }
     }
+    if (need_acc) f32_to_bf16_kernel<<<grid1(V * H), 256, 0, s>>>(p.dW_acc, static_cast<bf16_t *>(d_W), V * H);
+    return launch_status();
+}
+
+// ----------------------------------------------------------------------------
+// forward and backward in one call
+// ----------------------------------------------------------------------------
+// With the gradient of the total w.r.t. the loss known up front, nothing has to be formed
+// twice: the batch is walked in pieces of Tz tokens; the forward sweep of a piece also stores
+// its logits (fp16 offsets, 2 * V bytes per token), the piece's log-probs give the gradient
+// factors, one pass turns the stored logits of the piece's active tokens into bf16 logit
+// gradients, and the two contractions follow: three products of size T x V x H instead of four.
+// By default a piece's stored logits stay within kDzBudgetBytes, and so do its gradients.
+struct FbPlan {
+    int64_t Tz, T_pad, V_pad, V_blk, Kc, nVt, nblk_tok;
+    int nsplit;
+    double *count;
+    float *g, *z_target, *part_max, *part_sum, *offs, *dW_acc, *W32, *dx_part;
+    FwdPartial *partials;
+    int32_t *act_idx, *n_act;
+    float4 *tok;
+    uint16_t *Z;
+    bf16_t *dZ, *WT, *Xb, *Xs, *Ws, *Wvh;
+    void *Xc;
+    int dx_split;
+    size_t bytes;
+};
+
+static FbPlan plan_fb(const spo_pg_desc *d, int64_t chunk_tokens, void *ws, bool need_dw_acc, bool want_dx) {
+    FbPlan p;
+    p.T_pad = round_up(std::max<int64_t>(d->T, 1), TL::BN);
+    p.V_pad = round_up(d->V, kBK);
+    p.V_blk = round_up(d->V, TL::BM);
+    p.nVt = p.V_blk / TL::BM;
+    p.Kc = d->dtype == SPO_FP32 ? kSplitTerms * d->H : d->H;
+    // tokens per piece: a multiple of 4096 (16 splits x 16 token tiles = one round of workgroups
+    // of the sweep on 256 compute units) that keeps the stored logits within the budget, and the
+    // logit gradients likewise
+    int64_t tz = chunk_tokens > 0 ? round_up(chunk_tokens, TL::BN) : kDzBudgetBytes / (2 * p.V_blk) / 4096 * 4096;
+    if (tz < TL::BN) tz = TL::BN;
+    p.Tz = std::min(tz, p.T_pad);
+    // Vocabulary splits of a piece's sweep: a launch lasts (rounds of workgroups on the chip) x
+    // (tiles of the longest workgroup); among the multiples of 8 that fill the chip the count
+    // with the shortest launch, else what the sweep chooses for small problems.
+    p.nsplit = 0;
+    const int64_t nTz = p.Tz / TL::BN;
+    int64_t best = 0;
+    for (int ns = kSweepSplits; ns <= 64 && ns <= p.nVt && nTz * kSweepSplits >= kChipCUs; ns += 8) {
+        const int64_t cost = ceil_div(nTz * ns, kChipCUs) * ceil_div(p.nVt, ns);
+        if (!p.nsplit || cost < best) {
+            best = cost;
+            p.nsplit = ns;
+        }
+    }
+    p.nsplit = SweepMap(nTz, p.nVt, p.nsplit).nsplit;
+    p.nblk_tok = p.T_pad / kTokThreads;
+    static_assert(TL::BN % kTokThreads == 0, "pieces start at a block of the per-token kernels");
+    Arena a(ws);
+    p.count = a.take<double>(1);
+    p.g = a.take<float>(p.T_pad);
+    p.z_target = a.take<float>(p.T_pad);
+    p.partials = a.take<FwdPartial>(p.nblk_tok);
+    p.part_max = a.take<float>(static_cast<size_t>(p.nsplit) * p.Tz);
+    p.part_sum = a.take<float>(static_cast<size_t>(p.nsplit) * p.Tz);
+    p.offs = a.take<float>(static_cast<size_t>(p.nVt) * TL::WGM * p.Tz);
+    p.act_idx = a.take<int32_t>(p.Tz);
+    p.n_act = a.take<int32_t>(1);
+    p.tok = a.take<float4>(p.Tz);
+    const int64_t dx_tiles = (p.Tz / TL::BN) * ceil_div(d->H, TL::BM);
+    p.dx_split = want_dx && dx_tiles * 4 < kChipCUs * 3 ? static_cast<int>(std::min<int64_t>(8, kChipCUs / dx_tiles)) : 1;
+    p.dx_part = p.dx_split > 1 ? a.take<float>(static_cast<size_t>(p.dx_split) * p.Tz * d->H) : nullptr;
+    p.Xc = a.take<char>(static_cast<size_t>(p.Tz) * d->H * (d->dtype == SPO_FP32 ? 4 : 2));
+    p.WT = want_dx ? a.take<bf16_t>(static_cast<size_t>(d->H) * p.V_blk) : nullptr;
+    p.Z = a.take<uint16_t>(static_cast<size_t>(p.Tz) * p.V_blk);
+    p.dZ = a.take<bf16_t>(static_cast<size_t>(p.Tz) * p.V_blk);
+    p.Xb = p.Xs = p.Ws = p.Wvh = nullptr;
+    p.dW_acc = p.W32 = nullptr;
+    if (d->dtype == SPO_FP32) {
+        p.Xb = a.take<bf16_t>(static_cast<size_t>(p.Tz) * d->H);
+        p.Xs = a.take<bf16_t>(static_cast<size_t>(p.Tz) * p.Kc);
+        p.Ws = a.take<bf16_t>(static_cast<size_t>(d->V) * p.Kc);
+        if (d->w_layout == SPO_W_HV) p.W32 = a.take<float>(static_cast<size_t>(d->V) * d->H);
+    } else if (d->w_layout == SPO_W_HV) {
+        p.Wvh = a.take<bf16_t>(static_cast<size_t>(d->V) * d->H);
+    }
+    if (need_dw_acc) p.dW_acc = a.take<float>(static_cast<size_t>(d->V) * d->H);
+    p.bytes = a.used;
+    return p;
+}
+
+int fused_fwd_bwd_workspace(const spo_pg_desc *d, int64_t chunk_tokens, size_t *bytes) {
+    *bytes = plan_fb(d, chunk_tokens, nullptr, true, true).bytes;  // sized for the larger case
+    return SPO_OK;
+}
+
+int fused_fwd_bwd(const spo_pg_desc *d, float grad_loss, float *loss, float *logp, float *lse, float *stats,
+                  void *d_hidden, int d_hidden_dtype, void *d_W, int d_W_dtype, int accumulate_dW,
+                  int64_t chunk_tokens, void *ws, size_t ws_bytes, hipStream_t s) {
+    int rc = check_fused(d);
+    if (rc) return rc;
+    if (accumulate_dW && d_W && d_W_dtype != SPO_FP32) return SPO_EINVAL;
+    const bool need_acc = d_W && d_W_dtype == SPO_BF16;
+    const FbPlan p = plan_fb(d, chunk_tokens, ws, need_acc, d_hidden != nullptr);
+    if (ws_bytes < p.bytes) return SPO_EWORKSPACE;
+    if ((rc = set_lds_limit())) return rc;
+    const int64_t H = d->H, V = d->V, T = d->T;
+    float *dW32 = need_acc ? p.dW_acc : static_cast<float *>(d_W);
+    if (T == 0) {
+        if (d_W && !accumulate_dW) {
+            const int64_t words = d_W_dtype == SPO_FP32 ? V * H : V * H / 2;
+            fill_zero_kernel<<<grid1(words), 256, 0, s>>>(static_cast<uint32_t *>(d_W), words);
+        }
+        loss_finalize_kernel<<<1, kTokThreads, 0, s>>>(p.partials, 0, loss, stats);
+        return launch_status();
+    }
+    mask_count_kernel<<<1, 1024, 0, s>>>(d->mask, T, p.count);
+    // the head as the kernels read it: one row per vocabulary entry for the logits, one row per
+    // hidden unit (blocked over the vocabulary) for dHidden
+    const char *Wk;
+    if (d->dtype == SPO_FP32) {
+        const float *w32 = static_cast<const float *>(d->W);
+        if (d->w_layout == SPO_W_HV) {
+            transpose_f32_kernel<<<dim3(grid1(H, 64), grid1(V, 64)), 256, 0, s>>>(w32, H, V, p.W32);
+            w32 = p.W32;
+        }
+        split_expand_kernel<<<grid1(V * H), 256, 0, s>>>(w32, V, H, p.Ws, 0);
+        Wk = reinterpret_cast<const char *>(p.Ws);
+        if (d_hidden) launch_transpose(w32, V, H, H, p.WT, p.V_blk, H, 0, s);
+        target_logit_kernel<float><<<grid1(T, 4), 256, 0, s>>>(static_cast<const float *>(d->hidden), w32, H, V, T,
+                                                               d->target, p.z_target);
+    } else {
+        const bf16_t *Wvh = static_cast<const bf16_t *>(d->W);
+        if (d->w_layout == SPO_W_HV) {
+            launch_transpose(static_cast<const bf16_t *>(d->W), H, V, V, p.Wvh, H, V, H, s);
+            Wvh = p.Wvh;
+        }
+        Wk = reinterpret_cast<const char *>(Wvh);
+        if (d_hidden) launch_transpose(Wvh, V, H, H, p.WT, p.V_blk, H, 0, s);
+        target_logit_kernel<bf16_t><<<grid1(T, 4), 256, 0, s>>>(static_cast<const bf16_t *>(d->hidden), Wvh, H, V, T,
+                                                                d->target, p.z_target);
+    }
+    if (d_hidden) {  // rows of tokens without a gradient stay zero
+        const int64_t words = T * H / (d_hidden_dtype == SPO_FP32 ? 1 : 2);
+        fill_zero_kernel<<<grid1(words), 256, 0, s>>>(static_cast<uint32_t *>(d_hidden), words);
+    }
+    const size_t x_elt = d->dtype == SPO_FP32 ? 4 : 2, dx_elt = d_hidden_dtype == SPO_FP32 ? 4 : 2;
+    for (int64_t t0 = 0, c = 0; t0 < T; t0 += p.Tz, ++c) {
+        const int64_t Tv = std::min(p.Tz, T - t0), Tzp = round_up(Tv, TL::BN);
+        const char *Xpiece = static_cast<const char *>(d->hidden) + t0 * H * x_elt;
+        const char *Xk = Xpiece;
+        if (d->dtype == SPO_FP32) {
+            split_expand_kernel<<<grid1(Tv * H), 256, 0, s>>>(reinterpret_cast<const float *>(Xpiece), Tv, H, p.Xs, 1);
+            Xk = reinterpret_cast<const char *>(p.Xs);
+        }
+        const SweepMap map(Tzp / TL::BN, p.nVt, p.nsplit);
+        {
+            ScopedKernelTimer timer(kTimeFwdSweep, s);
+            fwd_sweep_kernel<true><<<static_cast<unsigned>(map.blocks()), TL::NT, kSweepLds, s>>>(
+                Wk, p.Kc * 2, V, Xk, p.Kc * 2, Tv, static_cast<int>(p.Kc / kBK), map.nsplit, map.nTt, map.nVt, Tzp,
+                p.part_max, p.part_sum, p.Z, Tzp * kBlockK, p.offs);
+        }
+        token_loss_kernel<<<grid1(Tv, kTokThreads), kTokThreads, 0, s>>>(
+            p.part_max, p.part_sum, map.nsplit, Tzp, p.z_target + t0, Tv, d->old_logp + t0, d->mask ? d->mask + t0 : nullptr,
+            d->adv_norm, d->cu_seqlens, d->B, d->eps_low, d->eps_high, logp + t0, lse + t0, p.partials + t0 / kTokThreads,
+            t0);
+        if (!d_hidden && !d_W) continue;
+        grad_scale_kernel<<<grid1(Tzp, kTokThreads), kTokThreads, 0, s>>>(
+            logp + t0, d->old_logp + t0, d->mask ? d->mask + t0 : nullptr, d->adv_norm, d->cu_seqlens, d->B, Tv, Tzp,
+            d->eps_low, d->eps_high, grad_loss, p.count, p.g + t0, t0);
+        compact_active_kernel<<<1, 1024, 0, s>>>(p.g + t0, Tv, p.act_idx, p.n_act);
+        const bf16_t *Xrows;
+        if (d->dtype == SPO_FP32) {
+            float *xc = static_cast<float *>(p.Xc);
+            gather_chunk_kernel<float><<<static_cast<unsigned>(Tzp), 256, 0, s>>>(
+                reinterpret_cast<const float *>(Xpiece), H, p.act_idx, p.n_act, 0, Tzp, d->target + t0, lse + t0, p.g + t0,
+                xc, p.tok);
+            if (d_W) f32_to_bf16_kernel<<<grid1(Tzp * H), 256, 0, s>>>(xc, p.Xb, Tzp * H);
+            Xrows = p.Xb;
+        } else {
+            bf16_t *xc = static_cast<bf16_t *>(p.Xc);
+            gather_chunk_kernel<bf16_t><<<static_cast<unsigned>(Tzp), 256, 0, s>>>(
+                reinterpret_cast<const bf16_t *>(Xpiece), H, p.act_idx, p.n_act, 0, Tzp, d->target + t0, lse + t0,
+                p.g + t0, xc, p.tok);
+            Xrows = xc;
+        }
+        {
+            constexpr int per_wg = 8;
+            const int64_t n_blk = p.V_blk / kBlockK;
+            ScopedKernelTimer timer(kTimeLogitsToDz, s);
+            dz_from_logits_kernel<<<dim3(static_cast<unsigned>(Tzp / 32), grid1(n_blk, per_wg)), 256, 0, s>>>(
+                p.Z, Tzp * kBlockK, p.offs, Tzp, p.act_idx, p.n_act, Tzp, p.tok, p.dZ,
+                Tzp * kBlockK, n_blk, per_wg);
+        }
+        if (d_hidden) {
+            ScopedKernelTimer timer(kTimeDHidden, s);
+            launch_gemm<false>(p.dZ, kBlockK, Tzp, p.WT, kBlockK, H, p.V_pad, static_cast<char *>(d_hidden) + t0 * H * dx_elt, H,
+                               d_hidden_dtype, 0, p.n_act, 0, kLimitRows, p.act_idx, Tzp * kBlockK, H * kBlockK, s,
+                               p.dx_split, p.dx_part);
+        }
+        if (d_W) {
+            const int acc = (c > 0 || accumulate_dW) ? 1 : 0;
+            ScopedKernelTimer timer(kTimeDW, s);
+            if (d->w_layout == SPO_W_VH)
+                launch_gemm<true>(p.dZ, kBlockK, V, Xrows, H, H, Tzp, dW32, H, SPO_FP32, acc, p.n_act, 0, kLimitK, nullptr,
+                                  Tzp * kBlockK, 0, s);
+            else
+                launch_gemm<true>(Xrows, H, H, p.dZ, kBlockK, V, Tzp, dW32, V, SPO_FP32, acc, p.n_act, 0, kLimitK, nullptr,
+                                  0, Tzp * kBlockK, s);
+        }
+    }
+    loss_finalize_kernel<<<1, kTokThreads, 0, s>>>(p.partials, ceil_div(T, kTokThreads), loss, stats);
     if (need_acc) f32_to_bf16_kernel<<<grid1(V * H), 256, 0, s>>>(p.dW_acc, static_cast<bf16_t *>(d_W), V * H);
     return launch_status();
 }

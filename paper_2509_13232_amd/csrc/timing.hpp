@@ -13,7 +13,8 @@ enum KernelClass {
     kTimeDW = 3,          // fused backward: dW += dZ^T X
     kTimeLogitsFwd = 4,   // logits-in forward row pass
     kTimeLogitsBwd = 5,   // logits-in backward row pass
-    kTimeClasses = 6
+    kTimeLogitsToDz = 6,  // one-call forward + backward: stored logits -> dZ
+    kTimeClasses = 7
 };
 
 bool timing_enabled();

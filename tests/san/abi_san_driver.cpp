@@ -86,6 +86,14 @@ int main() {
     EXPECT(spo_pg_loss_bwd(&d, f, f, 1.0f, f, 7, f, SPO_FP32, 0, nullptr, 0, ws, 1 << 20, nullptr), SPO_EINVAL);
     EXPECT(spo_pg_loss_bwd(&d, f, f, 1.0f, f, SPO_BF16, f, SPO_BF16, 1, nullptr, 0, ws, 1 << 20, nullptr), SPO_EINVAL);
     EXPECT(spo_pg_loss_bwd(&d, f, f, 1.0f, f, SPO_BF16, f, SPO_FP32, 0, nullptr, 0, ws, 16, nullptr), SPO_EWORKSPACE);
+    EXPECT(spo_pg_loss_fwd_bwd_workspace_bytes(&d, 0) > 0, 1);
+    EXPECT(spo_pg_loss_fwd_bwd_workspace_bytes(&d, -1), 0);
+    EXPECT(spo_pg_loss_fwd_bwd(&d, 1.0f, f, f, f, nullptr, f, SPO_BF16, f, SPO_FP32, 0, -5, ws, 1 << 20, nullptr), SPO_EINVAL);
+    EXPECT(spo_pg_loss_fwd_bwd(&d, 1.0f, f, f, f, nullptr, f, 7, f, SPO_FP32, 0, 0, ws, 1 << 20, nullptr), SPO_EINVAL);
+    EXPECT(spo_pg_loss_fwd_bwd(&d, 1.0f, f, f, f, nullptr, f, SPO_BF16, f, SPO_BF16, 1, 0, ws, 1 << 20, nullptr), SPO_EINVAL);
+    EXPECT(spo_pg_loss_fwd_bwd(&d, 1.0f, nullptr, f, f, nullptr, f, SPO_BF16, f, SPO_FP32, 0, 0, ws, 1 << 20, nullptr), SPO_ENULL);
+    EXPECT(spo_pg_loss_fwd_bwd(&d, 1.0f, f, f, f, nullptr, f, SPO_BF16, f, SPO_FP32, 0, 0, ws, 16, nullptr), SPO_EWORKSPACE);
+    EXPECT(spo_pg_loss_fwd_bwd(&d, 1.0f, f, f, f, nullptr, f, SPO_BF16, f, SPO_FP32, 0, 0, odd, 1 << 20, nullptr), SPO_EINVAL);
     d.H = 100;
     EXPECT(spo_pg_loss_fwd(&d, f, f, f, nullptr, ws, 1 << 20, nullptr), SPO_EUNSUPPORTED);
     d.H = 128; d.eps_low = -0.1f;
@@ -98,6 +106,8 @@ int main() {
     d.dtype = SPO_BF16; d.logits = f; d.hidden = d.W = nullptr; d.H = 0;
     EXPECT(spo_pg_loss_fwd_workspace_bytes(&d) > 0, 1);
     EXPECT(spo_pg_loss_fwd(&d, f, f, f, nullptr, ws, 16, nullptr), SPO_EWORKSPACE);
+    EXPECT(spo_pg_loss_fwd_bwd_workspace_bytes(&d, 0), 0);
+    EXPECT(spo_pg_loss_fwd_bwd(&d, 1.0f, f, f, f, nullptr, f, SPO_BF16, f, SPO_FP32, 0, 0, ws, 1 << 20, nullptr), SPO_EUNSUPPORTED);
 
     // timing aid
     EXPECT(spo_kernel_timing_enable(0), SPO_OK);

@@ -89,6 +89,20 @@ def test_host_side_argument_checks(L):
     assert L.spo_pg_loss_bwd(C.byref(d), one, one, 1.0, one, 1, one, 1, 1, None, 0, one, 1 << 40, None) == -1  # bf16 accumulate
     assert L.spo_pg_loss_bwd(C.byref(d), one, one, 1.0, one, 7, one, 0, 0, None, 0, one, 1 << 40, None) == -1  # bad dtype
     assert L.spo_pg_loss_bwd(C.byref(d), None, one, 1.0, one, 1, one, 0, 0, None, 0, one, 1 << 40, None) == -2
+    # forward and backward in one call: the checks of both
+    fb = L.spo_pg_loss_fwd_bwd
+    assert L.spo_pg_loss_fwd_bwd_workspace_bytes(C.byref(d), 0) > 0
+    assert L.spo_pg_loss_fwd_bwd_workspace_bytes(C.byref(d), -1) == 0
+    assert fb(C.byref(d), 1.0, one, one, one, None, one, 1, one, 1, 1, 0, one, 1 << 40, None) == -1   # bf16 accumulate
+    assert fb(C.byref(d), 1.0, one, one, one, None, one, 7, one, 0, 0, 0, one, 1 << 40, None) == -1   # bad dtype
+    assert fb(C.byref(d), 1.0, None, one, one, None, one, 1, one, 0, 0, 0, one, 1 << 40, None) == -2  # no loss
+    assert fb(C.byref(d), 1.0, one, one, one, None, one, 1, one, 0, 0, -3, one, 1 << 40, None) == -1  # chunk < 0
+    assert fb(C.byref(d), 1.0, one, one, one, None, one, 1, one, 0, 0, 0, None, 0, None) == -4        # no workspace
+    assert fb(C.byref(d), 1.0, one, one, one, None, one, 1, one, 0, 0, 0, one, 16, None) == -4        # too small
+    d.logits = 256
+    assert fb(C.byref(d), 1.0, one, one, one, None, one, 1, one, 0, 0, 0, one, 1 << 40, None) == -5   # logits-in form
+    assert L.spo_pg_loss_fwd_bwd_workspace_bytes(C.byref(d), 0) == 0
+    d.logits = None
     d.hidden = None
     assert L.spo_pg_loss_fwd(C.byref(d), one, one, one, None, one, 1 << 30, None) == -2
     d.hidden = 256
@@ -99,3 +113,7 @@ def test_host_side_argument_checks(L):
     big8k = L.spo_pg_loss_bwd_workspace_bytes(C.byref(d), 8192)
     big32k = L.spo_pg_loss_bwd_workspace_bytes(C.byref(d), 32768)
     assert small < big8k < big32k < 40 << 30
+    # one call: a piece's stored logits and its logit gradients, each within 8 GiB by default
+    fb0 = L.spo_pg_loss_fwd_bwd_workspace_bytes(C.byref(d), 0)
+    fb8k = L.spo_pg_loss_fwd_bwd_workspace_bytes(C.byref(d), 8192)
+    assert fb8k < fb0 < 24 << 30 and fb8k > big8k

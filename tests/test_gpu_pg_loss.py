@@ -26,11 +26,24 @@ MID = wl.scaled(wl.CONFIGS["C2"], name="mid", H=256, V=3000, mask_span=(4, 40))
 MID_LENGTHS = [37, 300, 1, 255, 120]  # T = 713: three token tiles, ragged tail; V: 11 tiles + 184
 
 
-def run_fwd_bwd(spo, case, w_layout=0, chunk_tokens=0, dx_dtype=torch.float32, dw_dtype=torch.float32):
+@pytest.fixture(params=[False, True], ids=["fwd_then_bwd", "one_call"])
+def one_call(request):
+    """The two ways to the gradients: spo_pg_loss_fwd followed by spo_pg_loss_bwd (the logits are
+    formed twice), or spo_pg_loss_fwd_bwd (formed once and kept, piece by piece, as fp16)."""
+    return request.param
+
+
+def run_fwd_bwd(spo, case, w_layout=0, chunk_tokens=0, dx_dtype=torch.float32, dw_dtype=torch.float32,
+                one_call=False):
     desc = case.to_gpu(spo, w_layout)
-    fwd = spo.spo_pg_loss_fwd(desc)
-    dx, dw = spo.spo_pg_loss_bwd(desc, fwd[1], fwd[2], 1.0, d_hidden_dtype=dx_dtype, d_W_dtype=dw_dtype,
-                                 chunk_tokens=chunk_tokens)
+    if one_call:
+        *fwd, dx, dw = spo.spo_pg_loss_fwd_bwd(desc, 1.0, d_hidden_dtype=dx_dtype, d_W_dtype=dw_dtype,
+                                               chunk_tokens=chunk_tokens)
+        fwd = tuple(fwd)
+    else:
+        fwd = spo.spo_pg_loss_fwd(desc)
+        dx, dw = spo.spo_pg_loss_bwd(desc, fwd[1], fwd[2], 1.0, d_hidden_dtype=dx_dtype, d_W_dtype=dw_dtype,
+                                     chunk_tokens=chunk_tokens)
     torch.cuda.synchronize()
     if w_layout == 1:
         dw = dw.t()
@@ -38,13 +51,13 @@ def run_fwd_bwd(spo, case, w_layout=0, chunk_tokens=0, dx_dtype=torch.float32, d
 
 
 @pytest.mark.parametrize("w_layout", [0, 1])
-def test_tiny_spo_step_fp32(spo, oracle, w_layout):
+def test_tiny_spo_step_fp32(spo, oracle, w_layout, one_call):
     cfg = wl.CONFIGS["C1"]
-    say(f"fused fp32 C1 T=512 H=128 V=1000 w_layout={w_layout}")
+    say(f"fused fp32 C1 T=512 H=128 V=1000 w_layout={w_layout} one_call={one_call}")
     case = Case(cfg)
     assert case.T == 512
     case.set_old_from_oracle(oracle)
-    fwd, dx, dw = run_fwd_bwd(spo, case, w_layout=w_layout)
+    fwd, dx, dw = run_fwd_bwd(spo, case, w_layout=w_layout, one_call=one_call)
     check_forward(case, oracle, fwd, atol_logp=2e-5)
     rb = oracle.pg_loss_bwd(*case.oracle_inputs(), *case.eps)
     assert rel_l2(f64(dx), rb["d_hidden"]) < GRAD_TOL
@@ -53,11 +66,11 @@ def test_tiny_spo_step_fp32(spo, oracle, w_layout):
 
 @pytest.mark.parametrize("w_layout", [0, 1])
 @pytest.mark.parametrize("w_scale,mask_frac", [(1.0, 0.0), (1.0, 0.25), (30.0, 0.25)])
-def test_fused_bf16_matches_oracle(spo, oracle, w_layout, w_scale, mask_frac):
-    say(f"fused bf16 mid T=713 H=256 V=3000 w_layout={w_layout} w_scale={w_scale} mask={mask_frac}")
+def test_fused_bf16_matches_oracle(spo, oracle, w_layout, w_scale, mask_frac, one_call):
+    say(f"fused bf16 mid T=713 H=256 V=3000 w_layout={w_layout} w_scale={w_scale} mask={mask_frac} one_call={one_call}")
     case = Case(MID, MID_LENGTHS, w_scale=w_scale, mask_frac=mask_frac)
     case.set_old_from_oracle(oracle)
-    fwd, dx, dw = run_fwd_bwd(spo, case, w_layout)
+    fwd, dx, dw = run_fwd_bwd(spo, case, w_layout, one_call=one_call)
     ref = check_forward(case, oracle, fwd)
     assert 0 < ref["active"].sum() < case.T          # both branches of the min occur
     rb = oracle.pg_loss_bwd(*case.oracle_inputs(), *case.eps)
@@ -85,33 +98,36 @@ def test_fused_bf16_matches_oracle(spo, oracle, w_layout, w_scale, mask_frac):
     del Hd
 
 
-def test_backward_chunks_and_output_dtypes(spo, oracle):
-    say("fused bf16 mid, chunk_tokens=256 (3 chunks), bf16 outputs")
+def test_backward_chunks_and_output_dtypes(spo, oracle, one_call):
+    say(f"fused bf16 mid, chunk_tokens=256 (3 chunks), bf16 outputs, one_call={one_call}")
     case = Case(MID, MID_LENGTHS, mask_frac=0.25)
     case.set_old_from_oracle(oracle)
     rb = oracle.pg_loss_bwd(*case.oracle_inputs(), *case.eps)
-    _, dx1, dw1 = run_fwd_bwd(spo, case, chunk_tokens=256)
-    _, dx2, dw2 = run_fwd_bwd(spo, case, chunk_tokens=0)
+    f1, dx1, dw1 = run_fwd_bwd(spo, case, chunk_tokens=256, one_call=one_call)
+    f2, dx2, dw2 = run_fwd_bwd(spo, case, chunk_tokens=0, one_call=one_call)
+    check_forward(case, oracle, f1)
+    assert torch.allclose(f1[1], f2[1], atol=1e-5, rtol=0)            # a token's log-prob does not depend on the pieces
     assert rel_l2(f64(dx1), rb["d_hidden"]) < GRAD_TOL and rel_l2(f64(dw1), rb["d_W"]) < GRAD_TOL
     assert rel_l2(f64(dx1), f64(dx2)) < 1e-5           # rows depend on the chunking only through the order of fp32 sums
     assert rel_l2(f64(dw1), f64(dw2)) < 1e-5           # fp32 partial sums in another order
-    _, dx3, dw3 = run_fwd_bwd(spo, case, chunk_tokens=512, dx_dtype=torch.bfloat16, dw_dtype=torch.bfloat16)
+    _, dx3, dw3 = run_fwd_bwd(spo, case, chunk_tokens=512, dx_dtype=torch.bfloat16, dw_dtype=torch.bfloat16,
+                              one_call=one_call)
     assert dx3.dtype == torch.bfloat16 and dw3.dtype == torch.bfloat16
     assert rel_l2(f64(dx3), rb["d_hidden"]) < GRAD_TOL and rel_l2(f64(dw3), rb["d_W"]) < GRAD_TOL
 
 
 @pytest.mark.parametrize("w_layout", [0, 1])
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
-def test_head_gradient_on_ragged_shapes(spo, oracle, w_layout, dtype):
+def test_head_gradient_on_ragged_shapes(spo, oracle, w_layout, dtype, one_call):
     # dW contracts over tokens from rows of dZ and of the hidden states: a vocabulary that is
     # neither a multiple of the tile nor of the 8-element pieces the rows are fetched in, a
     # hidden size below one tile, a token count with a ragged last tile.  Element-wise check:
     # a misplaced column or a piece fetched past the end of a row shows up in single entries.
-    say(f"fused {dtype} ragged T=300 H=192 V=1003 w_layout={w_layout}")
+    say(f"fused {dtype} ragged T=300 H=192 V=1003 w_layout={w_layout} one_call={one_call}")
     cfg = wl.scaled(MID, name="ragged", H=192, V=1003, dtype=dtype)
     case = Case(cfg, [130, 170])
     case.set_old_from_oracle(oracle)
-    fwd, dx, dw = run_fwd_bwd(spo, case, w_layout)
+    fwd, dx, dw = run_fwd_bwd(spo, case, w_layout, one_call=one_call)
     check_forward(case, oracle, fwd, atol_logp=2e-4 if dtype == "bf16" else 2e-5)
     rb = oracle.pg_loss_bwd(*case.oracle_inputs(), *case.eps)
     assert dw.shape == (1003, 192)
@@ -132,14 +148,14 @@ def test_head_gradient_on_ragged_shapes(spo, oracle, w_layout, dtype):
     ([150, 150], 2049, 256, 0, 0),   # one past eight vocabulary tiles
     ([40], 300, 320, 1, 0),          # hidden size between one and two tiles
 ])
-def test_corner_shapes_match_oracle(spo, oracle, lengths, V, H, w_layout, chunk):
+def test_corner_shapes_match_oracle(spo, oracle, lengths, V, H, w_layout, chunk, one_call):
     # sizes that sit on, just below and just above the tile, block and fetch-piece boundaries of
     # the contraction kernels, forward and both gradients against the oracle
-    say(f"fused bf16 corner T={sum(lengths)} H={H} V={V} w_layout={w_layout} chunk={chunk}")
+    say(f"fused bf16 corner T={sum(lengths)} H={H} V={V} w_layout={w_layout} chunk={chunk} one_call={one_call}")
     cfg = wl.scaled(MID, name="corner", H=H, V=V)
     case = Case(cfg, lengths)
     case.set_old_from_oracle(oracle)
-    fwd, dx, dw = run_fwd_bwd(spo, case, w_layout, chunk_tokens=chunk)
+    fwd, dx, dw = run_fwd_bwd(spo, case, w_layout, chunk_tokens=chunk, one_call=one_call)
     check_forward(case, oracle, fwd)
     rb = oracle.pg_loss_bwd(*case.oracle_inputs(), *case.eps)
     assert dw.shape == (V, H) and dx.shape == (sum(lengths), H)
@@ -157,18 +173,18 @@ DEEP_LENGTHS = [9000, 7000, 12001, 5000, 6999]  # T = 40000: 157 token tiles, th
 
 @pytest.mark.timeout(600)
 @pytest.mark.parametrize("w_layout,w_scale", [(0, 1.0), (1, 1.0), (0, 30.0)])
-def test_dense_deep_token_contraction_of_dW(spo, oracle, w_layout, w_scale):
+def test_dense_deep_token_contraction_of_dW(spo, oracle, w_layout, w_scale, one_call):
     # The head gradient contracts over tokens.  Here nothing is masked, so every chunk of 16384
     # tokens is one launch with 256 steps of the contraction, and the three chunks add into the
     # same fp32 d_W (read-modify-write across launches), as in the benchmark configuration.
     # Every entry of d_W and d_hidden is compared with the oracle; the softmax part of d_W
     # (d_W minus the rank-one terms of the sampled tokens) is compared on its own, because with
     # flat logits it hides inside the total; w_scale = 30 makes it as large as the target part.
-    say(f"fused bf16 deep T=40000 H=320 V=1100 chunk=16384 w_layout={w_layout} w_scale={w_scale}")
+    say(f"fused bf16 deep T=40000 H=320 V=1100 chunk=16384 w_layout={w_layout} w_scale={w_scale} one_call={one_call}")
     case = Case(DEEP, DEEP_LENGTHS, w_scale=w_scale)
     assert case.T == 40000 and case.mask is None
     case.set_old_from_oracle(oracle)
-    fwd, dx, dw = run_fwd_bwd(spo, case, w_layout, chunk_tokens=16384)
+    fwd, dx, dw = run_fwd_bwd(spo, case, w_layout, chunk_tokens=16384, one_call=one_call)
     ref = check_forward(case, oracle, fwd)
     assert ref["active"].sum() > 2 * 16384                   # three chunks of active tokens
     rb = oracle.pg_loss_bwd(*case.oracle_inputs(), *case.eps)
@@ -191,25 +207,25 @@ def test_dense_deep_token_contraction_of_dW(spo, oracle, w_layout, w_scale):
         assert rel_l2(soft_gpu, soft_ref) < 2 * GRAD_TOL
     # the same gradients from one chunk that holds every token: only the order of the fp32 sums differs
     # (of dW over the chunks, of dHidden over the parts a small chunk's vocabulary contraction is cut into)
-    _, dx1, dw1 = run_fwd_bwd(spo, case, w_layout, chunk_tokens=0)
+    _, dx1, dw1 = run_fwd_bwd(spo, case, w_layout, chunk_tokens=0, one_call=one_call)
     assert rel_l2(f64(dx1), got_dx) < 1e-5 and rel_l2(f64(dw1), got_dw) < 1e-4
-    _, dx2, dw2 = run_fwd_bwd(spo, case, w_layout, chunk_tokens=16384)
+    _, dx2, dw2 = run_fwd_bwd(spo, case, w_layout, chunk_tokens=16384, one_call=one_call)
     assert torch.equal(dx2, dx) and torch.equal(dw2, dw if w_layout == 0 else dw)   # same call, same bits
 
 
 @pytest.mark.parametrize("keep,chunk", [(256, 256), (257, 256), (1, 0), (300, 512), (511, 256)])
-def test_backward_runs_over_active_tokens_only(spo, oracle, keep, chunk):
+def test_backward_runs_over_active_tokens_only(spo, oracle, keep, chunk, one_call):
     # A sparse loss mask: the backward gathers the tokens that carry a gradient and works on
     # that list, `keep` of them here, chosen to end exactly on, one past, and far from the
     # boundaries of token tiles and chunks.  Rows of all other tokens must be exact zeros.
-    say(f"fused bf16 mid, {keep} unmasked tokens, chunk_tokens={chunk}")
+    say(f"fused bf16 mid, {keep} unmasked tokens, chunk_tokens={chunk} one_call={one_call}")
     case = Case(MID, MID_LENGTHS)
     case.set_old_from_oracle(oracle)
     rng = np.random.default_rng(keep)
     live = np.sort(rng.choice(case.T, keep, replace=False))
     case.mask = np.zeros(case.T, np.uint8)
     case.mask[live] = 1
-    fwd, dx, dw = run_fwd_bwd(spo, case, chunk_tokens=chunk)
+    fwd, dx, dw = run_fwd_bwd(spo, case, chunk_tokens=chunk, one_call=one_call)
     check_forward(case, oracle, fwd)
     rb = oracle.pg_loss_bwd(*case.oracle_inputs(), *case.eps)
     assert rel_l2(f64(dx), rb["d_hidden"]) < GRAD_TOL and rel_l2(f64(dw), rb["d_W"]) < GRAD_TOL
@@ -232,12 +248,12 @@ def test_cu_seqlens_may_start_anywhere(spo, oracle):
     assert torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])
 
 
-def test_results_are_bitwise_reproducible(spo, oracle):
-    say("fused bf16 mid, determinism")
+def test_results_are_bitwise_reproducible(spo, oracle, one_call):
+    say(f"fused bf16 mid, determinism, one_call={one_call}")
     case = Case(MID, MID_LENGTHS)
     case.set_old_from_oracle(oracle)
-    a = run_fwd_bwd(spo, case)
-    b = run_fwd_bwd(spo, case)
+    a = run_fwd_bwd(spo, case, chunk_tokens=256, one_call=one_call)
+    b = run_fwd_bwd(spo, case, chunk_tokens=256, one_call=one_call)
     assert torch.equal(a[0][0], b[0][0]) and torch.equal(a[0][1], b[0][1])
     assert torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])
 
@@ -275,12 +291,12 @@ def test_mini_batches_accumulate_into_dW(spo, oracle):
     assert rel_l2(f64(dW), ref_dw) < GRAD_TOL
 
 
-def test_degenerate_inputs(spo, oracle):
-    say("fused: all tokens masked")
+def test_degenerate_inputs(spo, oracle, one_call):
+    say(f"fused: all tokens masked, one_call={one_call}")
     case = Case(MID, [40, 60], mask_frac=0.5)
     case.set_old_from_oracle(oracle)
     case.mask = np.zeros(case.T, np.uint8)
-    fwd, dx, dw = run_fwd_bwd(spo, case)
+    fwd, dx, dw = run_fwd_bwd(spo, case, one_call=one_call)
     assert fwd[0].item() == 0.0 and not dx.any() and not dw.any()
     ref = oracle.pg_loss_fwd(*case.oracle_inputs(), *case.eps)
     np.testing.assert_allclose(f64(fwd[1]), ref["logp"], atol=2e-4)     # log-probs are still produced
@@ -288,14 +304,14 @@ def test_degenerate_inputs(spo, oracle):
     tiny = wl.scaled(MID, name="tiny", H=64, V=100)
     case = Case(tiny, [1], adv=[1.5])
     case.set_old_from_oracle(oracle)
-    fwd, dx, dw = run_fwd_bwd(spo, case)
+    fwd, dx, dw = run_fwd_bwd(spo, case, one_call=one_call)
     check_forward(case, oracle, fwd)
     rb = oracle.pg_loss_bwd(*case.oracle_inputs(), *case.eps)
     assert rel_l2(f64(dx), rb["d_hidden"]) < GRAD_TOL and rel_l2(f64(dw), rb["d_W"]) < GRAD_TOL
     say("fused: empty responses inside the batch")
     case = Case(MID, [0, 70, 0, 0, 33, 0])
     case.set_old_from_oracle(oracle)
-    fwd, dx, dw = run_fwd_bwd(spo, case)
+    fwd, dx, dw = run_fwd_bwd(spo, case, one_call=one_call)
     check_forward(case, oracle, fwd)
     rb = oracle.pg_loss_bwd(*case.oracle_inputs(), *case.eps)
     assert rel_l2(f64(dx), rb["d_hidden"]) < GRAD_TOL and rel_l2(f64(dw), rb["d_W"]) < GRAD_TOL
@@ -303,9 +319,12 @@ def test_degenerate_inputs(spo, oracle):
     case = Case(MID, [0, 0])
     case.old = np.zeros(0, np.float32)
     desc = case.to_gpu(spo)
-    loss, logp, lse, stats = spo.spo_pg_loss_fwd(desc)
     dW = torch.full((MID.V, MID.H), 7.0, device="cuda")
-    spo.spo_pg_loss_bwd(desc, logp, lse, 1.0, d_W=dW, want_d_hidden=False)
+    if one_call:
+        loss, logp, lse, stats, _, _ = spo.spo_pg_loss_fwd_bwd(desc, 1.0, d_W=dW, want_d_hidden=False)
+    else:
+        loss, logp, lse, stats = spo.spo_pg_loss_fwd(desc)
+        spo.spo_pg_loss_bwd(desc, logp, lse, 1.0, d_W=dW, want_d_hidden=False)
     torch.cuda.synchronize()
     assert loss.item() == 0.0 and stats[0].item() == 0.0 and not dW.any()
 
