@@ -359,11 +359,19 @@ def main() -> int:
                                                            workspace=ws5))
         us_adv = timed(lambda: spo.spo_advantages(a5, b5, i5, r5))
         us_upd = timed(lambda: spo.spo_tracker_update(a5, b5, i5, r5, k5, c5.d_half, c5.rho_min, c5.rho_max))
+        # advantages of a batch of 2^20 responses (ids repeat): one workgroup against the many-workgroup form
+        big = 1 << 20
+        ib = torch.randint(0, c5.N, (big,), dtype=torch.int32, device=dev)
+        rb = (torch.rand(big, device=dev) < 0.4).float()
+        ws_adv = torch.empty(spo.lib().spo_advantages_workspace_bytes(big), dtype=torch.uint8, device=dev)
+        us_adv_big1 = timed(lambda: spo.spo_advantages(a5, b5, ib, rb), reps=3)
+        us_adv_big = timed(lambda: spo.spo_advantages(a5, b5, ib, rb, workspace=ws_adv))
         scan_bytes = c5.N * (8 + 8 + 8)   # alpha, beta read in two passes (8 B each), 8-byte CDF written
         small = {
             "workload": f"C5: {c5.N} tracked prompts, batch {c5.B}",
             "sample_without_replacement_us": round(us_sample, 1), "sample_with_replacement_us": round(us_sample_r, 1),
             "advantages_us": round(us_adv, 1), "tracker_update_us": round(us_upd, 1),
+            "advantages_1M_responses_us": {"one_workgroup": round(us_adv_big1, 1), "with_workspace": round(us_adv_big, 1)},
             "weight_scan_GBps": round(scan_bytes / (us_sample_r * 1e-6) / 1e9, 1),
             "note": "host-visible time per call on the launch stream (several small launches each); "
                     "weight_scan_GBps counts 24 B per prompt over the with-replacement call"}

@@ -129,13 +129,21 @@ int spo_sample_prompts_static(const float *alpha, const float *beta, int64_t N, 
  * info         optional int32[1]: 0, or 1 if some idx[k] lies outside [0, N).  Such an
  *              id is never used as an index: its advantage is NaN, and so are the
  *              batch statistics and every normalised value.
- * Statistics are accumulated in fp64 in a fixed order (bitwise reproducible).
- * Limits: 1 <= B < 2^31.
+ * ws           optional, spo_advantages_workspace_bytes(B) bytes, 256-byte aligned.
+ *              Without it one workgroup does all the work (three passes over the
+ *              batch: right for the batches of the paper, slow beyond ~10^5
+ *              responses); with it, batches of 16384 responses or more are spread
+ *              over the chip (partial sums of 4096 responses each, added in a fixed
+ *              order).  Both forms are bitwise reproducible; between them the
+ *              statistics agree to fp64 rounding.
+ * Statistics are accumulated in fp64 in a fixed order.
+ * Limits: 1 <= B < 2^31.  Errors: ws too small -> SPO_EWORKSPACE.
  * ------------------------------------------------------------------------- */
+size_t spo_advantages_workspace_bytes(int32_t B);
 int spo_advantages(const float *alpha, const float *beta, int64_t N, const int32_t *idx,
                    const float *reward, int32_t B, int ddof, float eps_norm, int use_baseline,
-                   float *adv_raw, float *adv_norm, float *stats, int32_t *info,
-                   spo_stream_t stream);
+                   float *adv_raw, float *adv_norm, float *stats, int32_t *info, void *ws,
+                   size_t ws_bytes, spo_stream_t stream);
 
 /* Diagnostics of the unnormalised advantages that the paper's analysis tracks
  * (Experiments, "Signal Efficiency and Information Loss" and "Signal Stability and

@@ -21,7 +21,7 @@ SPO_SAMPLE_STATIC_MAX_N = 1 << 20
 EXPORTS = (
     "spo_status_string", "spo_sample_prompts_workspace_bytes", "spo_sample_prompts",
     "spo_sample_prompts_static",
-    "spo_advantages", "spo_advantage_diagnostics", "spo_tracker_update_workspace_bytes", "spo_tracker_update",
+    "spo_advantages_workspace_bytes", "spo_advantages", "spo_advantage_diagnostics", "spo_tracker_update_workspace_bytes", "spo_tracker_update",
     "spo_tracker_update_ema",
     "spo_tracker_init",
     "spo_pg_loss_fwd_workspace_bytes", "spo_pg_loss_fwd",
@@ -72,7 +72,9 @@ def lib():
         L.spo_sample_prompts_static.restype = C.c_int
         L.spo_sample_prompts_static.argtypes = [vp, vp, i64, i32, f64, u64, u64, C.c_int, u32, vp, vp, vp]
         L.spo_advantages.restype = C.c_int
-        L.spo_advantages.argtypes = [vp, vp, i64, vp, vp, i32, C.c_int, f32, C.c_int, vp, vp, vp, vp, vp]
+        L.spo_advantages.argtypes = [vp, vp, i64, vp, vp, i32, C.c_int, f32, C.c_int, vp, vp, vp, vp, vp, sz, vp]
+        L.spo_advantages_workspace_bytes.restype = sz
+        L.spo_advantages_workspace_bytes.argtypes = [i32]
         L.spo_advantage_diagnostics.restype = C.c_int
         L.spo_advantage_diagnostics.argtypes = [vp, vp, i32, f32, f32, vp, vp]
         L.spo_tracker_update.restype = C.c_int
@@ -190,7 +192,7 @@ def spo_sample_prompts_static(alpha, beta, B, eps_explore=0.05, seed=0, iteratio
 
 
 # --------------------------------------------------------------- advantages
-def spo_advantages(alpha, beta, idx, reward, ddof=0, eps_norm=0.0, use_baseline=True, info=None):
+def spo_advantages(alpha, beta, idx, reward, ddof=0, eps_norm=0.0, use_baseline=True, info=None, workspace=None):
     """Returns (adv_raw, adv_norm, stats).  info: optional int32[1] tensor that receives the range flag."""
     B = reward.numel()
     _want(info, torch.int32, "info", 1)
@@ -205,7 +207,8 @@ def spo_advantages(alpha, beta, idx, reward, ddof=0, eps_norm=0.0, use_baseline=
     st = torch.empty(2, dtype=torch.float32, device=reward.device)
     _check(lib().spo_advantages(_ptr(alpha), _ptr(beta), N, _ptr(idx), _ptr(reward), B, int(ddof),
                                 float(eps_norm), int(bool(use_baseline)), _ptr(raw), _ptr(nrm), _ptr(st),
-                                _ptr(info), _stream()), "spo_advantages")
+                                _ptr(info), _ptr(workspace), workspace.numel() if workspace is not None else 0,
+                                _stream()), "spo_advantages")
     return raw, nrm, st
 
 

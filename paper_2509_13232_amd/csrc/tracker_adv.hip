@@ -171,6 +171,24 @@ tracker_init_kernel(const float *__restrict__ v0, int64_t N, double n0, float *_
     beta[i] = static_cast<float>(n0 * (1.0 - v));
 }
 
+// Raw advantage of response k in fp64.  An id outside [0, N) reads nothing: its baseline is NaN
+// (so are the batch statistics) and it is flagged.
+__device__ __forceinline__ double raw_advantage(const float *__restrict__ alpha, const float *__restrict__ beta,
+                                                const int32_t *__restrict__ idx, const float *__restrict__ reward,
+                                                int use_baseline, int64_t N, int32_t *__restrict__ info, int k) {
+    double v = 0.0;
+    if (use_baseline) {
+        const int64_t i = idx[k];
+        if (i < 0 || i >= N) {
+            if (info) info[0] = kInfoRange;
+            return __builtin_nan("");
+        }
+        const double a = alpha[i];
+        v = beta ? a / (a + static_cast<double>(beta[i])) : a;
+    }
+    return static_cast<double>(reward[k]) - v;
+}
+
 // One workgroup: raw advantages, then mean and standard deviation in fp64 with a
 // fixed reduction order, then the normalised values.  The centred second pass
 // avoids the cancellation of the sum-of-squares shortcut.
@@ -182,20 +200,7 @@ advantages_kernel(const float *__restrict__ alpha, const float *__restrict__ bet
                   double eps_norm, int use_baseline, float *__restrict__ adv_raw,
                   float *__restrict__ adv_norm, float *__restrict__ stats, int64_t N, int32_t *__restrict__ info) {
     __shared__ double scratch[kAdvThreads / kWave];
-    // an id outside [0, N) reads nothing: its baseline is NaN (so are the batch statistics) and it is flagged
-    auto raw = [&](int k) -> double {
-        double v = 0.0;
-        if (use_baseline) {
-            const int64_t i = idx[k];
-            if (i < 0 || i >= N) {
-                if (info) info[0] = kInfoRange;
-                return __builtin_nan("");
-            }
-            const double a = alpha[i];
-            v = beta ? a / (a + static_cast<double>(beta[i])) : a;
-        }
-        return static_cast<double>(reward[k]) - v;
-    };
+    auto raw = [&](int k) { return raw_advantage(alpha, beta, idx, reward, use_baseline, N, info, k); };
     if (info && threadIdx.x == 0) info[0] = 0;
     __syncthreads();
     double s = 0.0;
@@ -215,8 +220,67 @@ advantages_kernel(const float *__restrict__ alpha, const float *__restrict__ bet
     const double sigma = dn > 0.0 ? sqrt(ss / dn) : 0.0;
     const double den = sigma + eps_norm;
     for (int k = threadIdx.x; k < B; k += kAdvThreads)
-        adv_norm[k] = den > 0.0 ? static_cast<float>((raw(k) - mu) / den) : 0.0f;
+        adv_norm[k] = den == 0.0 ? 0.0f : static_cast<float>((raw(k) - mu) / den);  // den is >= 0, or NaN and says so
     if (stats && threadIdx.x == 0) {
+        stats[0] = static_cast<float>(mu);
+        stats[1] = static_cast<float>(sigma);
+    }
+}
+
+// The same over many workgroups, for large batches: three launches, each workgroup over kAdvSpan
+// responses.  part[0..nb) are the workgroups' sums of the raw advantages, part[nb..2nb) their
+// sums of centred squares; every workgroup adds the partial sums it needs in the same fixed
+// order, so all of them hold the same mean and deviation, bit for bit, in every run.  (The order
+// differs from the one-workgroup kernel's: the two agree to fp64 rounding, not bitwise.)
+constexpr int kAdvSpan = 4096;
+
+__device__ __forceinline__ double ordered_total(const double *__restrict__ part, int nb, double *scratch) {
+    double s = 0.0;
+    for (int i = threadIdx.x; i < nb; i += kAdvThreads) s += part[i];
+    return block_sum(s, scratch);
+}
+
+// phase 0: raw advantages and their partial sums; phase 1: partial sums of centred squares;
+// phase 2: normalised values and the statistics
+template <int Phase>
+__global__ void __launch_bounds__(kAdvThreads)
+advantages_wide_kernel(const float *__restrict__ alpha, const float *__restrict__ beta,
+                       const int32_t *__restrict__ idx, const float *__restrict__ reward, int B, int ddof,
+                       double eps_norm, int use_baseline, float *__restrict__ adv_raw, float *__restrict__ adv_norm,
+                       float *__restrict__ stats, int64_t N, int32_t *__restrict__ info, double *__restrict__ part) {
+    __shared__ double scratch[kAdvThreads / kWave];
+    const int nb = gridDim.x;
+    const int k0 = blockIdx.x * kAdvSpan, k1 = k0 + kAdvSpan < B ? k0 + kAdvSpan : B;
+    auto raw = [&](int k) { return raw_advantage(alpha, beta, idx, reward, use_baseline, N, info, k); };
+    if (Phase == 0) {
+        double s = 0.0;
+        for (int k = k0 + threadIdx.x; k < k1; k += kAdvThreads) {
+            const double a = raw(k);
+            if (adv_raw) adv_raw[k] = static_cast<float>(a);
+            s += a;
+        }
+        s = block_sum(s, scratch);
+        if (threadIdx.x == 0) part[blockIdx.x] = s;
+        return;
+    }
+    const double mu = ordered_total(part, nb, scratch) / static_cast<double>(B);
+    if (Phase == 1) {
+        double ss = 0.0;
+        for (int k = k0 + threadIdx.x; k < k1; k += kAdvThreads) {
+            const double d = raw(k) - mu;
+            ss += d * d;
+        }
+        ss = block_sum(ss, scratch);
+        if (threadIdx.x == 0) part[nb + blockIdx.x] = ss;
+        return;
+    }
+    const double dn = static_cast<double>(B - ddof);
+    const double ss = ordered_total(part + nb, nb, scratch);
+    const double sigma = dn > 0.0 ? sqrt(ss / dn) : 0.0;
+    const double den = sigma + eps_norm;
+    for (int k = k0 + threadIdx.x; k < k1; k += kAdvThreads)
+        adv_norm[k] = den == 0.0 ? 0.0f : static_cast<float>((raw(k) - mu) / den);  // den is >= 0, or NaN and says so
+    if (stats && blockIdx.x == 0 && threadIdx.x == 0) {
         stats[0] = static_cast<float>(mu);
         stats[1] = static_cast<float>(sigma);
     }
@@ -327,15 +391,37 @@ extern "C" int spo_tracker_init(const float *v0, int64_t N, float rho_min, float
     return launch_status();
 }
 
+constexpr int kAdvWideMin = 4 * kAdvSpan;  // below this one workgroup is as fast
+
+extern "C" size_t spo_advantages_workspace_bytes(int32_t B) {
+    if (B < 1) return 0;
+    return static_cast<size_t>(2 * ceil_div(B, kAdvSpan)) * sizeof(double);
+}
+
 extern "C" int spo_advantages(const float *alpha, const float *beta, int64_t N, const int32_t *idx,
                               const float *reward, int32_t B, int ddof, float eps_norm,
                               int use_baseline, float *adv_raw, float *adv_norm, float *stats,
-                              int32_t *info, spo_stream_t stream) {
+                              int32_t *info, void *ws, size_t ws_bytes, spo_stream_t stream) {
     if (!reward || !adv_norm) return SPO_ENULL;
     if (use_baseline && (!alpha || !idx)) return SPO_ENULL;
     if (B < 1 || (use_baseline && N < 1) || ddof < 0 || ddof > 1 || !(eps_norm >= 0.0f))
         return SPO_EINVAL;
-    advantages_kernel<<<1, kAdvThreads, 0, as_stream(stream)>>>(
-        alpha, beta, idx, reward, B, ddof, eps_norm, use_baseline, adv_raw, adv_norm, stats, N, info);
+    if (ws && reinterpret_cast<uintptr_t>(ws) % 256 != 0) return SPO_EINVAL;
+    if (ws && ws_bytes < spo_advantages_workspace_bytes(B)) return SPO_EWORKSPACE;
+    hipStream_t s = as_stream(stream);
+    if (!ws || B < kAdvWideMin) {
+        advantages_kernel<<<1, kAdvThreads, 0, s>>>(alpha, beta, idx, reward, B, ddof, eps_norm, use_baseline, adv_raw,
+                                                    adv_norm, stats, N, info);
+        return launch_status();
+    }
+    const unsigned nb = static_cast<unsigned>(ceil_div(B, kAdvSpan));
+    double *part = static_cast<double *>(ws);
+    if (info) clear_info_kernel<<<1, 1, 0, s>>>(info);
+    advantages_wide_kernel<0><<<nb, kAdvThreads, 0, s>>>(alpha, beta, idx, reward, B, ddof, eps_norm, use_baseline,
+                                                        adv_raw, adv_norm, stats, N, info, part);
+    advantages_wide_kernel<1><<<nb, kAdvThreads, 0, s>>>(alpha, beta, idx, reward, B, ddof, eps_norm, use_baseline,
+                                                        adv_raw, adv_norm, stats, N, info, part);
+    advantages_wide_kernel<2><<<nb, kAdvThreads, 0, s>>>(alpha, beta, idx, reward, B, ddof, eps_norm, use_baseline,
+                                                        adv_raw, adv_norm, stats, N, info, part);
     return launch_status();
 }

@@ -44,10 +44,13 @@ int main() {
     EXPECT(spo_sample_prompts_static(f, nullptr, 4, 2, 0.05, 0, 0, 0, 0, i32, nullptr, nullptr), SPO_ENULL);
 
     // advantages, diagnostics, tracker
-    EXPECT(spo_advantages(nullptr, f, 4, i32, f, 1, 0, 0.0f, 1, nullptr, f, nullptr, nullptr, nullptr), SPO_ENULL);
-    EXPECT(spo_advantages(f, f, 4, i32, f, 0, 0, 0.0f, 1, nullptr, f, nullptr, nullptr, nullptr), SPO_EINVAL);
-    EXPECT(spo_advantages(f, f, 4, i32, f, 3, 2, 0.0f, 1, nullptr, f, nullptr, nullptr, nullptr), SPO_EINVAL);
-    EXPECT(spo_advantages(f, f, 4, i32, f, 3, 0, -1.0f, 1, nullptr, f, nullptr, nullptr, nullptr), SPO_EINVAL);
+    EXPECT(spo_advantages(nullptr, f, 4, i32, f, 1, 0, 0.0f, 1, nullptr, f, nullptr, nullptr, nullptr, 0, nullptr), SPO_ENULL);
+    EXPECT(spo_advantages(f, f, 4, i32, f, 0, 0, 0.0f, 1, nullptr, f, nullptr, nullptr, nullptr, 0, nullptr), SPO_EINVAL);
+    EXPECT(spo_advantages(f, f, 4, i32, f, 3, 2, 0.0f, 1, nullptr, f, nullptr, nullptr, nullptr, 0, nullptr), SPO_EINVAL);
+    EXPECT(spo_advantages(f, f, 4, i32, f, 3, 0, -1.0f, 1, nullptr, f, nullptr, nullptr, nullptr, 0, nullptr), SPO_EINVAL);
+    EXPECT(spo_advantages(f, f, 4, i32, f, 3, 0, 0.0f, 1, nullptr, f, nullptr, nullptr, ws, 8, nullptr), SPO_EWORKSPACE);
+    EXPECT(spo_advantages(f, f, 4, i32, f, 3, 0, 0.0f, 1, nullptr, f, nullptr, nullptr, odd, 1 << 20, nullptr), SPO_EINVAL);
+    EXPECT(spo_advantages_workspace_bytes(0), 0);
     EXPECT(spo_advantage_diagnostics(f, f, 4, 0.02f, 1e-4f, f, nullptr), SPO_EINVAL);
     EXPECT(spo_advantage_diagnostics(f, nullptr, 4, 1e-4f, 0.02f, f, nullptr), SPO_ENULL);
     EXPECT(spo_tracker_update_workspace_bytes(0), 0);

@@ -47,14 +47,16 @@ def test_host_side_argument_checks(L):
     assert L.spo_tracker_update(None, None, 4, None, None, None, 1, 0.25, 0.875, 0.96, 1, *tail) == -2
     assert L.spo_tracker_update_ema(None, None, 4, None, None, None, 1, 0.25, 0.875, 0.96, 1, *tail) == -2
     assert L.spo_tracker_update_ema(one, one, 4, one, one, one, 1, -1.0, 0.875, 0.96, 1, *tail) == -1
-    assert L.spo_advantages(None, None, 4, None, None, 1, 0, 0.0, 1, None, None, None, None, None) == -2
+    assert L.spo_advantages(None, None, 4, None, None, 1, 0, 0.0, 1, None, None, None, None, None, 0, None) == -2
     assert L.spo_sample_prompts(None, None, 4, 1, 0.05, 0, 0, 0, 0, None, None, None, 0, None) == -2
     # bad scalars
     assert L.spo_tracker_update(one, one, 4, one, one, one, 1, 0.0, 0.875, 0.96, 1, *tail) == -1
     assert L.spo_tracker_update(one, one, 4, one, one, one, 1, 0.25, 0.97, 0.96, 1, *tail) == -1
     assert L.spo_tracker_update(one, one, 4, one, one, one, 0, 0.25, 0.875, 0.96, 1, *tail) == -1
-    assert L.spo_advantages(one, one, 4, one, one, 0, 0, 0.0, 1, None, one, None, None, None) == -1
-    assert L.spo_advantages(one, one, 4, one, one, 3, 2, 0.0, 1, None, one, None, None, None) == -1
+    assert L.spo_advantages(one, one, 4, one, one, 0, 0, 0.0, 1, None, one, None, None, None, 0, None) == -1
+    assert L.spo_advantages(one, one, 4, one, one, 3, 2, 0.0, 1, None, one, None, None, None, 0, None) == -1
+    assert L.spo_advantages(one, one, 4, one, one, 3, 0, 0.0, 1, None, one, None, None, one, 8, None) == -4   # workspace too small
+    assert L.spo_advantages_workspace_bytes(1 << 20) == 2 * 256 * 8 and L.spo_advantages_workspace_bytes(0) == 0
     # repeated ids need the slot table; a table that is too small or misaligned is refused
     assert L.spo_tracker_update(one, one, 4, one, one, one, 1, 0.25, 0.875, 0.96, 0, *tail) == -4
     assert L.spo_tracker_update(one, one, 1000, one, one, one, 1, 0.25, 0.875, 0.96, 0, None, None, None, one, 256, None) == -4

@@ -163,6 +163,7 @@ def test_ids_out_of_range_or_repeated_are_flagged_not_followed(spo, oracle):
     raw, nrm, _ = spo.spo_advantages(dev(a), dev(b), dev(bad), dev(r), info=info)
     torch.cuda.synchronize()
     assert info.item() == 1 and np.isnan(raw.cpu().numpy()[~good]).all() and np.isfinite(raw.cpu().numpy()[good]).all()
+    assert torch.isnan(nrm).all()                                          # the batch statistics are NaN: nothing is normalised
     raw, nrm, _ = spo.spo_advantages(dev(a), dev(b), dev(idx), dev(r), info=info)
     torch.cuda.synchronize()
     assert info.item() == 0 and np.isfinite(nrm.cpu().numpy()).all()
@@ -203,6 +204,41 @@ def test_advantages_match_oracle(spo, oracle, name, n, ddof, eps_norm, baseline)
     # run-to-run bitwise reproducible
     _, nrm2, _ = spo.spo_advantages(dev(a), dev(b), dev(idx), dev(r), ddof, eps_norm, baseline)
     assert torch.equal(nrm, nrm2)
+
+
+@pytest.mark.parametrize("B", [16384, 100003, 1 << 20])
+@pytest.mark.parametrize("ddof,eps_norm,baseline", [(0, 0.0, True), (1, 1e-6, False)])
+def test_advantages_of_large_batches_over_many_workgroups(spo, oracle, B, ddof, eps_norm, baseline):
+    # with a workspace, batches of 16384 responses or more are spread over the chip: partial sums of
+    # 4096 responses, added in a fixed order (a ragged last part at B = 100003); ids repeat
+    cfg = wl.CONFIGS["C5"]
+    say(f"advantages, wide path, B={B} ddof={ddof} baseline={baseline}")
+    a, b = wl.tracker_state(cfg, 5)
+    rng = np.random.default_rng([wl.MASTER_SEED, B])
+    idx = rng.integers(0, cfg.N, B).astype(np.int32)
+    r = (rng.random(B) < 0.4).astype(np.float32)
+    eraw, enrm, (mu, sigma) = oracle.advantages(a, b, idx, r, ddof, float(np.float32(eps_norm)), baseline)
+    ws = torch.empty(spo.lib().spo_advantages_workspace_bytes(B), dtype=torch.uint8, device="cuda")
+    ga, gb, gi, gr = dev(a), dev(b), dev(idx), dev(r)
+    info = torch.full((1,), 7, dtype=torch.int32, device="cuda")
+    raw, nrm, st = spo.spo_advantages(ga, gb, gi, gr, ddof, eps_norm, baseline, info=info, workspace=ws)
+    torch.cuda.synchronize()
+    assert info.item() == 0
+    np.testing.assert_allclose(raw.cpu().numpy(), eraw, rtol=RTOL, atol=1e-7)
+    np.testing.assert_allclose(nrm.cpu().numpy(), enrm, rtol=RTOL, atol=1e-6)
+    np.testing.assert_allclose(st.cpu().numpy(), [mu, sigma], rtol=RTOL, atol=1e-7)
+    _, nrm2, st2 = spo.spo_advantages(ga, gb, gi, gr, ddof, eps_norm, baseline, workspace=ws)
+    assert torch.equal(nrm, nrm2) and torch.equal(st, st2)                  # bitwise reproducible
+    _, nrm1, st1 = spo.spo_advantages(ga, gb, gi, gr, ddof, eps_norm, baseline)   # one workgroup: same to fp64 rounding
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(nrm1.cpu().numpy(), nrm.cpu().numpy(), rtol=1e-6, atol=1e-7)
+    if baseline:    # an id out of range is flagged, not followed, here too
+        bad = idx.copy()
+        bad[B // 2] = cfg.N
+        info.zero_()
+        raw, nrm, _ = spo.spo_advantages(ga, gb, dev(bad), gr, ddof, eps_norm, baseline, info=info, workspace=ws)
+        torch.cuda.synchronize()
+        assert info.item() == 1 and torch.isnan(raw[B // 2]) and torch.isnan(nrm).all()
 
 
 def test_advantages_degenerate_batch(spo):
