@@ -632,16 +632,27 @@ gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, cons
                   int64_t ldb_bytes, int64_t N, int KT, void *__restrict__ out, int64_t ldo, int out_dtype,
                   int accumulate, const int32_t *__restrict__ n_act, int64_t row_base, int limit,
                   const int32_t *__restrict__ row_map, int64_t a_blk, int64_t b_blk, int nsplit,
-                  float *__restrict__ partials) {
+                  float *__restrict__ partials, int64_t tile_lo, int64_t tile_hi, int tail_parts) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     constexpr int bpt = TL::BM / kBlockK;  // blocks per tile edge
     static_assert(TL::BM % kBlockK == 0 && TL::BN == TL::BM, "a tile of a blocked operand is a whole number of blocks");
     static_assert(TL::WGM == 2 && TL::BN * 4 * (TL::BM / 2) <= TL::LDS_BYTES, "half a tile of fp32 fits the operand stages");
-    const TileOrder ord(ceil_div(M, TL::BM), ceil_div(N, TL::BN));
-    const int64_t per_part = ord.blocks();
-    const int part = static_cast<int>(blockIdx.x / per_part);
+    const int64_t tiles_n = ceil_div(N, TL::BN);
     int64_t tm, tn;
-    if (!ord.tile(blockIdx.x % per_part, tm, tn)) return;
+    int part;
+    if (tail_parts > 0) {  // tile tile_lo + i of the row-major order, part p: workgroup i * tail_parts + p
+        part = static_cast<int>(blockIdx.x % tail_parts);
+        const int64_t t = tile_lo + blockIdx.x / tail_parts;
+        if (t >= tile_hi) return;
+        tm = t / tiles_n;
+        tn = t % tiles_n;
+    } else {
+        const TileOrder ord(ceil_div(M, TL::BM), tiles_n);
+        const int64_t per_part = ord.blocks();
+        part = static_cast<int>(blockIdx.x / per_part);
+        if (!ord.tile(blockIdx.x % per_part, tm, tn)) return;
+        if (tm * tiles_n + tn >= tile_hi) return;  // left to the launch that cuts the last tiles along the contraction
+    }
     const int64_t m0 = tm * TL::BM, n0 = tn * TL::BN;
     int64_t m_end = M;
     if (n_act && limit == kLimitRows) {
@@ -651,11 +662,12 @@ gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, cons
     if (n_act && limit == kLimitK) {
         const int64_t k_rows = active_rows(n_act, row_base, static_cast<int64_t>(KT) * kBK);
         KT = __builtin_amdgcn_readfirstlane(static_cast<int>(ceil_div(k_rows, TL::BN) * (TL::BN / kBK)));
-        if (KT == 0 && accumulate) return;  // nothing to add
+        if (KT == 0 && accumulate && !tail_parts) return;  // nothing to add
     }
     int kt0 = 0;
-    if (nsplit > 1) {  // this part's run of k-steps
-        const int per = (KT + nsplit - 1) / nsplit;
+    const int parts = tail_parts > 0 ? tail_parts : nsplit;
+    if (parts > 1) {  // this part's run of k-steps
+        const int per = (KT + parts - 1) / parts;
         kt0 = part * per;
         KT = KT - kt0 < per ? KT - kt0 : per;
     }
@@ -664,8 +676,9 @@ gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, cons
     if (KT > 0) {
         if (KMajor) {
             const int64_t Mr = (M + 7) & ~int64_t(7), Nr = (N + 7) & ~int64_t(7);
-            TL::mainloop_kmajor(a_blk ? A + tm * bpt * a_blk : A, lda_bytes, a_blk ? 0 : m0, a_blk ? TL::BM : Mr,
-                                b_blk ? B + tn * bpt * b_blk : B, ldb_bytes, b_blk ? 0 : n0, b_blk ? TL::BN : Nr, KT, lds,
+            const char *Ak = A + kt0 * (kBK * lda_bytes), *Bk = B + kt0 * (kBK * ldb_bytes);  // rows are the contraction index
+            TL::mainloop_kmajor(a_blk ? Ak + tm * bpt * a_blk : Ak, lda_bytes, a_blk ? 0 : m0, a_blk ? TL::BM : Mr,
+                                b_blk ? Bk + tn * bpt * b_blk : Bk, ldb_bytes, b_blk ? 0 : n0, b_blk ? TL::BN : Nr, KT, lds,
                                 acc, a_blk, b_blk);
         } else {
             // k-step kt of an operand starts blk bytes (blocked) or one stage of 128 bytes (row-major) further on
@@ -674,33 +687,45 @@ gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, cons
                          KT, lds, acc);
         }
     }
-    if (nsplit > 1) {  // partial tiles: plain fp32 rows of N values, no row map
+    // where the tile goes: its place in the output, or (parts of a contraction) a plain fp32 tile
+    int64_t om0 = m0, on0 = n0, oN = N;
+    if (nsplit > 1) {  // partial results [part][M][N], no row map
         out = partials + static_cast<int64_t>(part) * M * N;
         ldo = N;
         out_dtype = SPO_FP32;
         accumulate = 0;
         row_map = nullptr;
     }
+    if (tail_parts > 0) {  // partial results [part][tile - tile_lo][BM][BN]
+        out = partials + (static_cast<int64_t>(part) * (tile_hi - tile_lo) + (tm * tiles_n + tn - tile_lo)) * (TL::BM * TL::BN);
+        ldo = TL::BN;
+        out_dtype = SPO_FP32;
+        accumulate = 0;
+        row_map = nullptr;
+        om0 = on0 = 0;
+        oN = TL::BN;
+        m_end = TL::BM;
+    }
     int lane = threadIdx.x & 63;
     asm volatile("" : "+v"(lane));  // not to be traced: nothing derived from it is to live through the main loop
     const int grp = lane >> 4, col = lane & 15;
     // whole groups of four columns can move as 16 (fp32) or 8 (bf16) bytes when the rows allow it
-    const bool vec = ldo % 4 == 0 && N % 4 == 0 && reinterpret_cast<uintptr_t>(out) % 16 == 0;
+    const bool vec = ldo % 4 == 0 && oN % 4 == 0 && reinterpret_cast<uintptr_t>(out) % 16 == 0;
     constexpr int HALF = TL::BM / 2, ROWS = HALF / TL::NWAVE;
     // adding to fp32 rows: the old values of a wavefront's rows are all requested before the half
     // tile is staged, so that their latency passes once per half tile and behind the staging
     const bool rmw = accumulate && out_dtype == SPO_FP32 && vec;
-    const int64_t n = n0 + 4 * lane;  // this lane's four columns
+    const int64_t n = on0 + 4 * lane;  // this lane's four columns
     __syncthreads();  // the operand stages are no longer read
 #pragma unroll 1
     for (int half = 0; half < 2; ++half) {
-        const int64_t m_first = m0 + half * HALF + TL::wave_id() * ROWS;  // this wavefront's rows of the half tile
+        const int64_t m_first = om0 + half * HALF + TL::wave_id() * ROWS;  // this wavefront's rows of the half tile
         float4 old[ROWS];
         if (rmw) {
 #pragma unroll
             for (int i = 0; i < ROWS; ++i) {
                 old[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-                if (m_first + i < m_end && n < N) {
+                if (m_first + i < m_end && n < oN) {
                     const int64_t m = row_map ? row_map[m_first + i] : m_first + i;
                     old[i] = *reinterpret_cast<const float4 *>(static_cast<const float *>(out) + m * ldo + n);
                 }
@@ -723,7 +748,7 @@ gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, cons
 #pragma unroll
             for (int i = 0; i < ROWS; ++i) {
                 const int row = TL::wave_id() * ROWS + i;
-                if (m_first + i >= m_end || n >= N) continue;
+                if (m_first + i >= m_end || n >= oN) continue;
                 const int64_t m = row_map ? row_map[m_first + i] : m_first + i;
                 const float4 v = *reinterpret_cast<const float4 *>(lds + row * (TL::BN * 4) +
                                                                    (((lane >> 2) ^ ((row >> 2) & 3)) << 6) + (lane & 3) * 16);
@@ -739,7 +764,7 @@ gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, cons
                 if (row_map) m = row_map[m];
                 const float4 v = *reinterpret_cast<const float4 *>(lds + row * (TL::BN * 4) +
                                                                    (((lane >> 2) ^ ((row >> 2) & 3)) << 6) + (lane & 3) * 16);
-                if (n >= N) continue;
+                if (n >= oN) continue;
                 if (out_dtype == SPO_FP32) {
                     float *o = static_cast<float *>(out) + m * ldo + n;
                     if (vec) {
@@ -748,7 +773,7 @@ gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, cons
                         const float e[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
                         for (int j = 0; j < 4; ++j)
-                            if (n + j < N) o[j] = accumulate ? o[j] + e[j] : e[j];
+                            if (n + j < oN) o[j] = accumulate ? o[j] + e[j] : e[j];
                     }
                 } else {
                     bf16_t *o = static_cast<bf16_t *>(out) + m * ldo + n;
@@ -758,7 +783,7 @@ gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, cons
                         const float e[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
                         for (int j = 0; j < 4; ++j)
-                            if (n + j < N) o[j] = f32_to_bf16(e[j]);
+                            if (n + j < oN) o[j] = f32_to_bf16(e[j]);
                     }
                 }
             }
@@ -787,6 +812,41 @@ reduce_split_kernel(const float *__restrict__ partials, int nsplit, int64_t M, i
     } else {
         *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(out) + mo * ldo + n) =
             make_uint2(pack_bf16x2_rn(s.x, s.y), pack_bf16x2_rn(s.z, s.w));
+    }
+}
+
+// The last, partly filled round of tiles of a launch, cut along the contraction (see launch_gemm):
+// out[m][n] (=|+=) the sum, in order, of partials[part][tile - tile_lo][m % BM][n % BN] over the
+// parts, for the tiles tile_lo <= tile < tile_hi of the row-major tile order.  Four values per thread.
+__global__ void __launch_bounds__(256)
+reduce_tail_kernel(const float *__restrict__ partials, int parts, int64_t tile_lo, int64_t tile_hi, int64_t M, int64_t N,
+                   float *__restrict__ out, int64_t ldo, int accumulate) {
+    constexpr int64_t per_tile = TL::BM * TL::BN / 4;
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    const int64_t tl = i / per_tile, r = (i % per_tile) / (TL::BN / 4), c = (i % (TL::BN / 4)) * 4;
+    const int64_t t = tile_lo + tl, tiles_n = ceil_div(N, TL::BN);
+    if (t >= tile_hi) return;
+    const int64_t m = (t / tiles_n) * TL::BM + r, n = (t % tiles_n) * TL::BN + c;
+    if (m >= M || n >= N) return;
+    float4 sum = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    for (int p = 0; p < parts; ++p) {
+        const float4 v = *reinterpret_cast<const float4 *>(
+            partials + ((static_cast<int64_t>(p) * (tile_hi - tile_lo) + tl) * TL::BM + r) * TL::BN + c);
+        sum = make_float4(sum.x + v.x, sum.y + v.y, sum.z + v.z, sum.w + v.w);
+    }
+    float *o = out + m * ldo + n;
+    const float e[4] = {sum.x, sum.y, sum.z, sum.w};
+    if (ldo % 4 == 0 && n + 3 < N && reinterpret_cast<uintptr_t>(out) % 16 == 0) {
+        float4 w = sum;
+        if (accumulate) {
+            const float4 old = *reinterpret_cast<const float4 *>(o);
+            w = make_float4(old.x + sum.x, old.y + sum.y, old.z + sum.z, old.w + sum.w);
+        }
+        *reinterpret_cast<float4 *>(o) = w;
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (n + j < N) o[j] = accumulate ? o[j] + e[j] : e[j];
     }
 }
 
@@ -980,6 +1040,7 @@ struct BwdPlan {
     float4 *tok;               // per-chunk records (g, -lse*log2e, target) of the gathered rows
     int dx_split;              // parts the dHidden contraction is cut into (1: not split)
     float *dx_part;            // their fp32 partial results [dx_split][Tc][H]
+    float *dw_tail;            // partial tiles of dW's last round (see launch_gemm)
     void *Xc;
     size_t bytes;
 };
@@ -1019,6 +1080,7 @@ static BwdPlan plan_bwd(const spo_pg_desc *d, int64_t chunk_tokens, void *ws, bo
         p.Wvh = a.take<bf16_t>(static_cast<size_t>(d->V) * d->H);
     }
     if (need_dw_acc) p.dW_acc = a.take<float>(static_cast<size_t>(d->V) * d->H);
+    p.dw_tail = a.take<float>(static_cast<size_t>(kChipCUs) * TL::BM * TL::BN);
     p.bytes = a.used;
     return p;
 }
@@ -1036,19 +1098,39 @@ static void launch_transpose(const SrcT *src, int64_t R, int64_t C, int64_t ld_s
                                                                                          R_pad, C_pad, ld_dst);
 }
 
+// A launch ends in a partly filled round of tiles when the tile count is no multiple of the
+// chip's compute units.  With `tail` (room for kTailTiles fp32 tiles; KMajor only, where the tile
+// count is known here) a short last round is launched on its own, every tile cut along the
+// contraction into as many parts as fill the chip, and reduce_tail_kernel adds the parts in
+// order: 9504 tiles on 256 units take 37 rounds and an eighth instead of 38.
+constexpr int kTailTiles = kChipCUs;
+
 template <bool KMajor>
 static void launch_gemm(const bf16_t *A, int64_t lda, int64_t M, const bf16_t *B, int64_t ldb, int64_t N, int64_t K,
                         void *out, int64_t ldo, int out_dtype, int accumulate, const int32_t *n_act, int64_t row_base,
                         int limit, const int32_t *row_map, int64_t a_blk_elems, int64_t b_blk_elems, hipStream_t s,
-                        int nsplit = 1, float *partials = nullptr) {
+                        int nsplit = 1, float *partials = nullptr, float *tail = nullptr) {
     const TileOrder ord(ceil_div(M, TL::BM), ceil_div(N, TL::BN));
+    const int64_t tiles = ord.nM * ord.nN, rem = tiles % kChipCUs;
+    int tail_parts = 0;
+    if (KMajor && tail && out_dtype == SPO_FP32 && tiles > kChipCUs && rem > 0 && rem <= kChipCUs / 4)
+        tail_parts = static_cast<int>(std::min<int64_t>(8, kChipCUs / rem));
+    const int64_t whole = tail_parts ? tiles - rem : tiles;
     gemm_store_kernel<KMajor><<<static_cast<unsigned>(ord.blocks() * nsplit), TL::NT, TL::LDS_BYTES, s>>>(
         reinterpret_cast<const char *>(A), lda * 2, M, reinterpret_cast<const char *>(B), ldb * 2, N,
         static_cast<int>(K / kBK), out, ldo, out_dtype, accumulate, n_act, row_base, limit, row_map, a_blk_elems * 2,
-        b_blk_elems * 2, nsplit, partials);
+        b_blk_elems * 2, nsplit, partials, 0, whole, 0);
     if (nsplit > 1)
         reduce_split_kernel<<<grid1(M * (N / 4)), 256, 0, s>>>(partials, nsplit, M, N, n_act, row_base, row_map, out, ldo,
                                                                out_dtype);
+    if (tail_parts) {
+        gemm_store_kernel<KMajor><<<static_cast<unsigned>(rem * tail_parts), TL::NT, TL::LDS_BYTES, s>>>(
+            reinterpret_cast<const char *>(A), lda * 2, M, reinterpret_cast<const char *>(B), ldb * 2, N,
+            static_cast<int>(K / kBK), out, ldo, out_dtype, accumulate, n_act, row_base, limit, row_map, a_blk_elems * 2,
+            b_blk_elems * 2, 1, tail, whole, tiles, tail_parts);
+        reduce_tail_kernel<<<grid1(rem * (TL::BM * TL::BN / 4)), 256, 0, s>>>(tail, tail_parts, whole, tiles, M, N,
+                                                                              static_cast<float *>(out), ldo, accumulate);
+    }
 }
 
 int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float grad_loss, void *d_hidden,
@@ -1142,10 +1224,10 @@ int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float g
             // contraction over the chunk's tokens, the row index of both dZ and the gathered hidden rows
             if (d->w_layout == SPO_W_VH)
                 launch_gemm<true>(p.dZ, kBlockK, V, Xrows, H, H, Tcp, dW32, H, SPO_FP32, acc, p.n_act, t0, kLimitK, nullptr,
-                                  Tcp * kBlockK, 0, s);
+                                  Tcp * kBlockK, 0, s, 1, nullptr, p.dw_tail);
             else
                 launch_gemm<true>(Xrows, H, H, p.dZ, kBlockK, V, Tcp, dW32, V, SPO_FP32, acc, p.n_act, t0, kLimitK, nullptr,
-                                  0, Tcp * kBlockK, s);
+                                  0, Tcp * kBlockK, s, 1, nullptr, p.dw_tail);
         }
     }
     if (need_acc) f32_to_bf16_kernel<<<grid1(V * H), 256, 0, s>>>(p.dW_acc, static_cast<bf16_t *>(d_W), V * H);
@@ -1165,7 +1247,7 @@ struct FbPlan {
     int64_t Tz, T_pad, V_pad, V_blk, Kc, nVt, nblk_tok;
     int nsplit;
     double *count;
-    float *g, *z_target, *part_max, *part_sum, *offs, *dW_acc, *W32, *dx_part;
+    float *g, *z_target, *part_max, *part_sum, *offs, *dW_acc, *W32, *dx_part, *dw_tail;
     FwdPartial *partials;
     int32_t *act_idx, *n_act;
     float4 *tok;
@@ -1234,6 +1316,7 @@ static FbPlan plan_fb(const spo_pg_desc *d, int64_t chunk_tokens, void *ws, bool
         p.Wvh = a.take<bf16_t>(static_cast<size_t>(d->V) * d->H);
     }
     if (need_dw_acc) p.dW_acc = a.take<float>(static_cast<size_t>(d->V) * d->H);
+    p.dw_tail = a.take<float>(static_cast<size_t>(kChipCUs) * TL::BM * TL::BN);
     p.bytes = a.used;
     return p;
 }
@@ -1352,10 +1435,10 @@ int fused_fwd_bwd(const spo_pg_desc *d, float grad_loss, float *loss, float *log
             ScopedKernelTimer timer(kTimeDW, s);
             if (d->w_layout == SPO_W_VH)
                 launch_gemm<true>(p.dZ, kBlockK, V, Xrows, H, H, Tzp, dW32, H, SPO_FP32, acc, p.n_act, 0, kLimitK, nullptr,
-                                  Tzp * kBlockK, 0, s);
+                                  Tzp * kBlockK, 0, s, 1, nullptr, p.dw_tail);
             else
                 launch_gemm<true>(Xrows, H, H, p.dZ, kBlockK, V, Tzp, dW32, V, SPO_FP32, acc, p.n_act, 0, kLimitK, nullptr,
-                                  0, Tzp * kBlockK, s);
+                                  0, Tzp * kBlockK, s, 1, nullptr, p.dw_tail);
         }
     }
     loss_finalize_kernel<<<1, kTokThreads, 0, s>>>(p.partials, ceil_div(T, kTokThreads), loss, stats);

@@ -167,6 +167,31 @@ def test_corner_shapes_match_oracle(spo, oracle, lengths, V, H, w_layout, chunk,
         assert not dx.any() and not dw.any()
 
 
+@pytest.mark.parametrize("w_layout,chunk", [(0, 0), (1, 512)])
+def test_last_round_of_dW_tiles_cut_along_the_tokens(spo, oracle, w_layout, chunk, one_call):
+    # 33 x 8 = 264 tiles of d_W on 256 compute units: the 8 tiles of the last round are launched on
+    # their own, each cut into 8 runs of tokens whose partial tiles are added in order (with chunk =
+    # 512 two launches add into d_W; 900 tokens are 16 k-steps: two per part in the first chunk, one or
+    # none in the second).  Every entry against the oracle, the tiles of the last round on their own.
+    V, H = 8200, 2048
+    say(f"fused bf16 T=900 H={H} V={V} w_layout={w_layout} chunk={chunk} one_call={one_call}: d_W tail tiles")
+    cfg = wl.scaled(MID, name="tail", H=H, V=V)
+    case = Case(cfg, [400, 500])
+    case.set_old_from_oracle(oracle)
+    fwd, dx, dw = run_fwd_bwd(spo, case, w_layout, chunk_tokens=chunk, one_call=one_call)
+    check_forward(case, oracle, fwd)
+    rb = oracle.pg_loss_bwd(*case.oracle_inputs(), *case.eps)
+    got = f64(dw)
+    assert rel_l2(f64(dx), rb["d_hidden"]) < GRAD_TOL and rel_l2(got, rb["d_W"]) < GRAD_TOL
+    scale = np.abs(rb["d_W"]).max()
+    np.testing.assert_allclose(got, rb["d_W"], atol=2e-2 * scale, rtol=0)
+    # in the row-major order of 256 x 256 tiles of the kernel's output ([V, H], or [H, V] for w_layout 1)
+    # the last 8 tiles are the last tile row: vocabulary entries from 8192 on, or hidden units from 1792 on
+    tail = (slice(8192, V), slice(None)) if w_layout == 0 else (slice(None), slice(1792, H))
+    assert np.abs(rb["d_W"][tail]).max() > 0
+    assert rel_l2(got[tail], rb["d_W"][tail]) < 2 * GRAD_TOL
+
+
 DEEP = wl.scaled(wl.CONFIGS["C2"], name="deep", H=320, V=1100)
 DEEP_LENGTHS = [9000, 7000, 12001, 5000, 6999]  # T = 40000: 157 token tiles, three chunks of 16384
 
