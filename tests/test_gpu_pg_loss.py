@@ -283,11 +283,11 @@ def test_results_are_bitwise_reproducible(spo, oracle, one_call):
     assert torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])
 
 
-def test_mini_batches_accumulate_into_dW(spo, oracle):
+def test_mini_batches_accumulate_into_dW(spo, oracle, one_call):
     # two mini-batches of whole responses, the batch-wide normalised advantages,
     # gradients accumulated into one d_W (one optimiser step per mini-batch is the
     # caller's business; the kernel only has to add)
-    say("fused bf16 mid, two mini-batches, accumulate_dW")
+    say(f"fused bf16 mid, two mini-batches, accumulate_dW, one_call={one_call}")
     case = Case(MID, MID_LENGTHS)
     case.set_old_from_oracle(oracle)
     h, w, tg, old, mk, ad, cu = case.oracle_inputs()
@@ -303,9 +303,13 @@ def test_mini_batches_accumulate_into_dW(spo, oracle):
         t0, t1 = int(cu[b0]), int(cu[b1])
         desc = spo.make_desc(hidden[t0:t1], W, target[t0:t1], oldg[t0:t1], None, adv[b0:b1],
                              cug[b0:b1 + 1], *case.eps)
-        loss, logp, lse, _ = spo.spo_pg_loss_fwd(desc)
-        dx, _ = spo.spo_pg_loss_bwd(desc, logp, lse, 1.0, d_hidden_dtype=torch.float32, d_W=dW,
-                                    accumulate_dW=True)
+        if one_call:
+            loss, _, _, _, dx, _ = spo.spo_pg_loss_fwd_bwd(desc, 1.0, d_hidden_dtype=torch.float32, d_W=dW,
+                                                           accumulate_dW=True)
+        else:
+            loss, logp, lse, _ = spo.spo_pg_loss_fwd(desc)
+            dx, _ = spo.spo_pg_loss_bwd(desc, logp, lse, 1.0, d_hidden_dtype=torch.float32, d_W=dW,
+                                        accumulate_dW=True)
         torch.cuda.synchronize()
         sub_cu = (cu[b0:b1 + 1] - cu[b0]).astype(np.int32)
         rf = oracle.pg_loss_fwd(h[t0:t1], w, tg[t0:t1], old[t0:t1], None, ad[b0:b1], sub_cu, *case.eps)
