@@ -144,8 +144,10 @@ def run_workload(spo, wl, torch, name, steps, warmup, chunk_tokens, want_d_hidde
     # gradient (unmasked and on the unclipped branch: stats[0] * (1 - stats[1]) of them).
     t_active = round(stats[0] * (1.0 - stats[1]))
     thv = {"fwd_sweep": 2.0 * T * H * V}            # flops of one contraction of a kernel class per step
+    # one call without a loss mask: the contractions run over every token (rows without a gradient are scaled by 0)
+    all_rows = one_call and tb.mask is None
     for k in MFMA_KERNELS[1:]:
-        thv[k] = 2.0 * t_active * H * V
+        thv[k] = 2.0 * (T if all_rows else t_active) * H * V
     kern = {}
     for k in MFMA_KERNELS:
         ms, n = times[k]
@@ -153,7 +155,7 @@ def run_workload(spo, wl, torch, name, steps, warmup, chunk_tokens, want_d_hidde
             kern[k] = {"ms_per_step": round(ms / steps, 3), "launches_per_step": n // steps,
                        "avg_launch_ms": round(ms / n, 4), "tflops": round(thv[k] / (ms / steps * 1e-3) / 1e12, 1)}
     executed = sum(thv[k] for k in kern)
-    useful = sum(thv[k] for k in kern if k != "bwd_recompute")
+    useful = 2.0 * T * H * V + 2 * 2.0 * t_active * H * V   # logits once, dHidden and dW of the tokens with a gradient
     # the pass from stored logits to logit gradients (one-call path): 2 V bytes read and 2 V written per active token
     V_blk = (V + 255) // 256 * 256
     for k in HBM_KERNELS:

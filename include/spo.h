@@ -299,25 +299,34 @@ int spo_pg_loss_bwd(const spo_pg_desc *d, const float *logp, const float *lse, f
  * grad_loss = d(total)/d(loss) before the forward: a loss that enters the total with
  * a fixed weight, which is how the policy-gradient objective is used (Method, the
  * PPO-Clip objective is the whole training loss).  Same results as spo_pg_loss_fwd
- * followed by spo_pg_loss_bwd, up to the rounding of the stored logits (below), at
+ * followed by spo_pg_loss_bwd, up to the rounding of what is stored (below), at
  * three contractions of size T x V x H instead of four: the logits are not formed
  * a second time.
  * The batch is walked in pieces of chunk_tokens tokens (rounded up to a multiple of
- * 256).  The forward sweep of a piece also stores its logits in the workspace: 2 * V
- * bytes per token, as fp16 of the logit minus an offset per (token, 128 vocabulary
- * entries): the largest logit the sweep has met for that token up to there.  An
- * entry within d of its row's largest logit is thus stored within d of zero, where
- * fp16 resolves d * 2^-11: the entries that carry the softmax are the most exact,
- * and the error this adds to a probability p is at most p * ln(1/p) * 2^-11.  (A
- * logit more than 65504 below its offset is stored as -inf: probability zero.)
- * The piece's log-probs then give the gradient factors, one pass turns the stored logits of
- * the tokens with a non-zero factor into bf16 logit gradients, and the two
- * contractions follow as in spo_pg_loss_bwd.  chunk_tokens = 0 lets the library
- * choose: the most tokens, in multiples of 4096, whose stored logits stay within
- * 8 GiB (24576 at V = 151936); their logit gradients take as much again.  Shorter
- * pieces cost more passes over d_W.
+ * 256).  The forward sweep of a piece also stores, at 2 * V bytes per token in the
+ * workspace, what the backward needs of its logits; the piece's log-probs then give
+ * the gradient factors and the two contractions follow.  What is stored depends on
+ * the desc:
+ *  - mask == NULL: bf16 of q[t][v] = exp(z[t][v] - r_t) with r_t = z[t][target_t] -
+ *    old_logp_t, known before the sweep; q = softmax / ratio_t lies near the
+ *    probabilities, and the logit gradient is c_t * (q - onehot / ratio_t) with
+ *    c_t = -g_t * ratio_t.  After the sweep one entry per token is rewritten and the
+ *    contractions read q as it is: d_hidden_t = c_t * (q_t W), d_W = q^T (c X).
+ *    Every token of the piece is multiplied, also those whose factor is zero (the
+ *    clipped ones); exponents are capped so that nothing stored is infinite.
+ *  - mask != NULL: fp16 of the logit minus an offset per (token, 128 vocabulary
+ *    entries), the largest logit the sweep has met for that token up to there.  An
+ *    entry within d of its row's largest logit is stored within d of zero, where
+ *    fp16 resolves d * 2^-11: the error this adds to a probability p is at most
+ *    p * ln(1/p) * 2^-11.  One pass then turns the stored logits of the tokens with a
+ *    non-zero factor into bf16 logit gradients (as much workspace again), and the
+ *    contractions run over those tokens only, as in spo_pg_loss_bwd.
+ * chunk_tokens = 0 lets the library choose: the most tokens, in multiples of 4096,
+ * whose stored values stay within 8 GiB (24576 at V = 151936).  Shorter pieces cost
+ * more passes over d_W.
  * Arguments as in spo_pg_loss_fwd and spo_pg_loss_bwd; d_hidden and d_W may each be
- * NULL.  Errors as there; a desc with logits != NULL -> SPO_EUNSUPPORTED. */
+ * NULL.  The workspace size depends on whether the desc has a mask.  Errors as
+ * there; a desc with logits != NULL -> SPO_EUNSUPPORTED. */
 size_t spo_pg_loss_fwd_bwd_workspace_bytes(const spo_pg_desc *d, int64_t chunk_tokens);
 int spo_pg_loss_fwd_bwd(const spo_pg_desc *d, float grad_loss, float *loss, float *logp,
                         float *lse, float *stats, void *d_hidden, int d_hidden_dtype,

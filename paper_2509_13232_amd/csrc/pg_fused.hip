@@ -298,7 +298,8 @@ struct SweepMap {
     __host__ __device__ int64_t first_tile(int split) const { return split * nVt / nsplit; }
 };
 
-constexpr int kSweepLds = TL::LDS_BYTES + TL::NT * 32;  // operand stages + the per-thread running state
+constexpr int kSweepLds = TL::LDS_BYTES + TL::NT * 32;       // operand stages + the per-thread running state
+constexpr int kSweepLdsProbs = TL::LDS_BYTES + TL::NT * 48;  // ... + the per-token references
 
 // Exchange between neighbouring groups of 16 lanes: v_permlane16_swap(a, b) swaps the odd groups
 // of a with the even groups of b.  With a, b the values a lane holds for two consecutive MFMA
@@ -318,17 +319,24 @@ __device__ __forceinline__ uint32_t pack_f16x2_rn(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, v);
 }
 
-// Emit = false: the forward proper; the logits exist in registers only.
-// Emit = true (the one-call forward + backward): every finished tile is also written out, as
-// fp16 of (logit - offset), in the blocked layout of the logit gradients: the logit of token n
-// (row of this launch), vocabulary entry v at Z + (v / 64) * z_blk + n * 64 + v % 64.  The
-// offset is the running maximum of the token over the 128 vocabulary rows per tile that the
-// wavefront has seen so far in its sweep, this tile included: one value per (vocabulary tile,
-// half of the tile, token), written to offs[(tile * 2 + half) * T_pad + n].  Stored values are
-// <= 0, and an entry within d of the row's largest logit is stored within d of zero, where
-// fp16 resolves 2^-11 * d: the entries that carry the softmax are the most exact ones.  Rows
-// past the vocabulary are stored as -inf.
-template <bool Emit>
+// Emit = kEmitNone: the forward proper; the logits exist in registers only.
+// The other two forms serve the one-call forward + backward: every finished tile is also
+// written out, in the blocked layout of the logit gradients (token n of this launch, vocabulary
+// entry v at Z + (v / 64) * z_blk + n * 64 + v % 64).
+// Emit = kEmitLogits: fp16 of (logit - offset).  The offset is the running maximum of the token
+// over the 128 vocabulary rows per tile that the wavefront has seen so far in its sweep, this
+// tile included: one value per (vocabulary tile, half of the tile, token), written to
+// offs[(tile * 2 + half) * T_pad + n].  Stored values are <= 0, and an entry within d of the
+// row's largest logit is stored within d of zero, where fp16 resolves 2^-11 * d: the entries
+// that carry the softmax are the most exact ones.  Rows past the vocabulary are stored as -inf.
+// Emit = kEmitProbs: bf16 of exp(logit - r_n), with r_n a per-token reference known before the
+// sweep (offs[n] = r_n * log2(e) on entry; see the host code for the choice that makes these
+// the softmax probabilities divided by the token's importance ratio).  The exponentials are the
+// ones the running sum needs anyway, times one factor per token and lane; exponents are capped
+// at 126 so that nothing stored is infinite.  Rows past the vocabulary are stored as zeros.
+constexpr int kEmitNone = 0, kEmitLogits = 1, kEmitProbs = 2;
+
+template <int Emit>
 __global__ void __launch_bounds__(TL::NT)
 fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const char *__restrict__ X,
                  int64_t ldx_bytes, int64_t T, int KT, int nsplit, int64_t nTt, int64_t nVt, int64_t T_pad,
@@ -349,10 +357,14 @@ fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const
     auto state = [&] {
         int tid = threadIdx.x;
         asm volatile("" : "+v"(tid));  // not to be traced: the address is formed anew at every use
-        return reinterpret_cast<float4 *>(lds + TL::LDS_BYTES) + 2 * tid;
+        return reinterpret_cast<float4 *>(lds + TL::LDS_BYTES) + (Emit == kEmitProbs ? 3 : 2) * tid;
     };
     state()[0] = make_float4(kNegBig, kNegBig, kNegBig, kNegBig);
     state()[1] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    if (Emit == kEmitProbs) {  // the references of this lane's four tokens: the workgroup keeps its token tile
+        const float *r = offs + n0 + TL::wave_n0() + (lane & 15);
+        state()[2] = make_float4(r[0], r[TL::MI], r[2 * TL::MI], r[3 * TL::MI]);
+    }
     // online log-sum-exp over the rows of one finished tile: three operations per logit
     // (multiply-add into the exponent, exponential, add) plus its share of the maximum
     auto reduce = [&](TL::Acc &acc, int64_t m0) {
@@ -383,7 +395,11 @@ fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const
 #pragma unroll
             for (int fm = 0; fm < TL::FM; ++fm)
 #pragma unroll
-                for (int r = 0; r < TL::ACC_R; ++r) s += __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r], kLog2e, c));
+                for (int r = 0; r < TL::ACC_R; ++r) {
+                    const float e = __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r], kLog2e, c));
+                    s += e;
+                    if (Emit == kEmitProbs) acc[fm][fn][r] = e;  // exp(logit - nm), rescaled to the reference by emit_probs
+                }
             s_run[fn] = s_run[fn] * __builtin_amdgcn_exp2f((m_run[fn] - nm) * kLog2e) + s;
             m_run[fn] = nm;
         }
@@ -430,13 +446,45 @@ fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const
             }
         }
     };
+    // kEmitProbs: acc holds exp(logit - m) with m this lane's running maximum (reduce left it there)
+    auto emit_probs = [&](TL::Acc &acc, int64_t vt) {
+        int l = threadIdx.x & 63;
+        asm volatile("" : "+v"(l));
+        const int grp = l >> 4, col = l & 15;
+        const float4 m4 = state()[0], r4 = state()[2];
+        const float m[TL::FN] = {m4.x, m4.y, m4.z, m4.w}, ref[TL::FN] = {r4.x, r4.y, r4.z, r4.w};
+        const int64_t wave_blk = vt * (TL::BM / kBlockK) + TL::wave_m0() / kBlockK;
+        const int piece = (grp & 1) * 16 + (grp & 2) * 4;
+#pragma unroll
+        for (int fn = 0; fn < TL::FN; ++fn) {
+            const float f = __builtin_amdgcn_exp2f(fminf(fmaf(m[fn], kLog2e, -ref[fn]), 126.0f));  // exp(m - r)
+            uint16_t *row = Z + (n0 + TL::wave_n0() + fn * TL::MI + col) * kBlockK + piece;
+#pragma unroll
+            for (int b = 0; b < TL::FM / 4; ++b) {
+                uint32_t lo[4], hi[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    lo[q] = pack_bf16x2_rn(acc[4 * b + q][fn][0] * f, acc[4 * b + q][fn][1] * f);
+                    hi[q] = pack_bf16x2_rn(acc[4 * b + q][fn][2] * f, acc[4 * b + q][fn][3] * f);
+                }
+                swap_lane_groups(lo[0], lo[1]);
+                swap_lane_groups(hi[0], hi[1]);
+                swap_lane_groups(lo[2], lo[3]);
+                swap_lane_groups(hi[2], hi[3]);
+                uint16_t *out = row + (wave_blk + b) * z_blk;
+                *reinterpret_cast<uint4 *>(out) = make_uint4(lo[0], hi[0], lo[1], hi[1]);
+                *reinterpret_cast<uint4 *>(out + kBlockK / 2) = make_uint4(lo[2], hi[2], lo[3], hi[3]);
+            }
+        }
+    };
     auto tile_ops = [&](int64_t vt) { return typename TL::Operands{W, ldw_bytes, vt * TL::BM, V, X, ldx_bytes, n0, T, 0, 0}; };
     for (int64_t vt = vt0; vt < vt1; ++vt) {
         TL::Acc acc;
         TL::zero(acc);
         TL::mainloop(tile_ops(vt), KT, lds, acc);
         reduce(acc, vt * TL::BM);
-        if (Emit) emit(acc, vt);
+        if (Emit == kEmitLogits) emit(acc, vt);
+        if (Emit == kEmitProbs) emit_probs(acc, vt);
     }
     // merge the lane groups that hold different rows of the same token, then the WGM
     // wavefronts that share a token column
@@ -612,7 +660,8 @@ recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V,
 // (rows = active_rows(n_act, row_base, .)): limit == kLimitRows keeps only the first
 // `rows` rows of A and stores row m at out row row_map[m] (dHidden: scatter back to the
 // tokens' own rows); limit == kLimitK contracts only over the first `rows` values of
-// the contraction index, rounded up to whole tiles of tokens (dW).
+// the contraction index, rounded up to whole tiles of tokens (dW).  row_scale != NULL (stores that
+// do not add to the output): row m of the product is multiplied by row_scale[m] on its way out.
 constexpr int kLimitRows = 1, kLimitK = 2;
 
 // With nsplit > 1 (plain form only) the contraction is cut into nsplit equal runs of k-steps;
@@ -632,7 +681,8 @@ gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, cons
                   int64_t ldb_bytes, int64_t N, int KT, void *__restrict__ out, int64_t ldo, int out_dtype,
                   int accumulate, const int32_t *__restrict__ n_act, int64_t row_base, int limit,
                   const int32_t *__restrict__ row_map, int64_t a_blk, int64_t b_blk, int nsplit,
-                  float *__restrict__ partials, int64_t tile_lo, int64_t tile_hi, int tail_parts) {
+                  float *__restrict__ partials, int64_t tile_lo, int64_t tile_hi, int tail_parts,
+                  const float *__restrict__ row_scale) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     constexpr int bpt = TL::BM / kBlockK;  // blocks per tile edge
     static_assert(TL::BM % kBlockK == 0 && TL::BN == TL::BM, "a tile of a blocked operand is a whole number of blocks");
@@ -761,9 +811,11 @@ gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, cons
                 const int row = TL::wave_id() * ROWS + i;
                 int64_t m = m_first + i;
                 if (m >= m_end) break;  // rows are in order: nothing further down either
+                const float sc = row_scale && nsplit == 1 ? row_scale[m] : 1.0f;  // (parts are scaled when they are added)
                 if (row_map) m = row_map[m];
-                const float4 v = *reinterpret_cast<const float4 *>(lds + row * (TL::BN * 4) +
-                                                                   (((lane >> 2) ^ ((row >> 2) & 3)) << 6) + (lane & 3) * 16);
+                float4 v = *reinterpret_cast<const float4 *>(lds + row * (TL::BN * 4) +
+                                                             (((lane >> 2) ^ ((row >> 2) & 3)) << 6) + (lane & 3) * 16);
+                v = make_float4(v.x * sc, v.y * sc, v.z * sc, v.w * sc);
                 if (n >= oN) continue;
                 if (out_dtype == SPO_FP32) {
                     float *o = static_cast<float *>(out) + m * ldo + n;
@@ -792,21 +844,26 @@ gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, cons
     }
 }
 
-// out[row_map[m]][n] = sum over the parts (in order) of partials[part][m][n] for m below the
-// number of active rows; four values per thread (N is a multiple of 4 here).
+// out[row_map[m]][n] = row_scale[m] * sum over the parts (in order) of partials[part][m][n] for m
+// below the number of active rows (n_act, row_map, row_scale may each be NULL: all M rows, in
+// place, unscaled); four values per thread (N is a multiple of 4 here).
 __global__ void __launch_bounds__(256)
 reduce_split_kernel(const float *__restrict__ partials, int nsplit, int64_t M, int64_t N,
                     const int32_t *__restrict__ n_act, int64_t row_base, const int32_t *__restrict__ row_map,
-                    void *__restrict__ out, int64_t ldo, int out_dtype) {
+                    void *__restrict__ out, int64_t ldo, int out_dtype, const float *__restrict__ row_scale) {
     const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
     const int64_t per_row = N / 4, m = i / per_row, n = (i % per_row) * 4;
-    if (m >= active_rows(n_act, row_base, M)) return;
+    if (m >= (n_act ? active_rows(n_act, row_base, M) : M)) return;
     float4 s = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     for (int p = 0; p < nsplit; ++p) {
         const float4 v = *reinterpret_cast<const float4 *>(partials + (static_cast<int64_t>(p) * M + m) * N + n);
         s = make_float4(s.x + v.x, s.y + v.y, s.z + v.z, s.w + v.w);
     }
-    const int64_t mo = row_map[m];
+    if (row_scale) {
+        const float sc = row_scale[m];
+        s = make_float4(s.x * sc, s.y * sc, s.z * sc, s.w * sc);
+    }
+    const int64_t mo = row_map ? row_map[m] : m;
     if (out_dtype == SPO_FP32) {
         *reinterpret_cast<float4 *>(static_cast<float *>(out) + mo * ldo + n) = s;
     } else {
@@ -854,7 +911,7 @@ reduce_tail_kernel(const float *__restrict__ partials, int parts, int64_t tile_l
 // one-call forward + backward: logit gradients from the logits the forward stored
 // ----------------------------------------------------------------------------
 // dZ[j][v] = g * ([v == target] - exp(z[v] - lse)) for the active tokens j of a piece of the
-// batch, from the fp16 offsets written by fwd_sweep_kernel<true> (z = stored value + offset of
+// batch, from the fp16 offsets written by fwd_sweep_kernel<kEmitLogits> (z = stored value + offset of
 // the entry's half tile), into the blocked bf16 layout the two contractions read.
 // Row j of the output is token act_idx[j] of the piece; tok[j] is its record (see
 // gather_chunk_kernel); rows from the number of active tokens up to the next multiple of 256
@@ -907,6 +964,80 @@ dz_from_logits_kernel(const uint16_t *__restrict__ Z, int64_t z_blk, const float
 }
 
 // ----------------------------------------------------------------------------
+// one-call forward + backward without a loss mask: the sweep stores what the contractions read
+// ----------------------------------------------------------------------------
+// The reference of token t is r_t = z_t[y_t] - old_logp_t: the log-sum-exp the token would have if
+// the policy had not moved since the behaviour policy sampled it.  Both terms are known before
+// the sweep (the logit of the sampled token costs one dot product).  Then
+//   Q[t][v] = exp(z[t][v] - r_t) = softmax(z_t)[v] / ratio_t,   ratio_t = exp(logp_t - old_logp_t),
+// lies near the probabilities whatever the logits' scale (bf16 keeps 8 bits of each entry), and
+//   dZ[t][v] = g_t ([v == y_t] - softmax[v]) = c_t (Q[t][v] - [v == y_t] / ratio_t),  c_t = -g_t ratio_t.
+// So once a piece's log-probs are known, one entry per token is rewritten (Q[t][y_t] = exp(old_logp_t)
+// by construction, so the new value is formed afresh in fp32 and rounded once) and the contractions
+// run on Q itself: dHidden_t = c_t (Q_t W), dW = Q^T (c X).  No pass over the stored tile is needed;
+// the price is that rows of tokens without a gradient (c_t = 0) are multiplied like the others,
+// which is why this form serves batches without a loss mask.
+
+// ref2[t] = r_t * log2(e); 0 where the token has no valid target logit, where old_logp is not
+// finite, and for the padding rows Tv <= t < Tzp (their stored rows stay finite and are multiplied by 0).
+__global__ void __launch_bounds__(kTokThreads)
+probs_reference_kernel(const float *__restrict__ z_target, const float *__restrict__ old_logp, int64_t Tv, int64_t Tzp,
+                       float *__restrict__ ref2) {
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * kTokThreads + threadIdx.x;
+    if (t >= Tzp) return;
+    float r = 0.0f;
+    if (t < Tv) {
+        r = (z_target[t] - old_logp[t]) * kLog2e;
+        if (!(fabsf(r) < 3.0e38f)) r = 0.0f;  // NaN or infinite
+    }
+    ref2[t] = r;
+}
+
+// c[t] = -g[t] * ratio_t (0 for tokens without a gradient and for the padding rows), and for the
+// tokens with a gradient Q[t][y_t] = exp(old_logp_t) - 1 / ratio_t.
+__global__ void __launch_bounds__(kTokThreads)
+probs_patch_kernel(const float *__restrict__ g, const float *__restrict__ logp, const float *__restrict__ old_logp,
+                   const int32_t *__restrict__ target, int64_t V, int64_t Tv, int64_t Tzp, uint16_t *__restrict__ Q,
+                   int64_t q_blk, float *__restrict__ c) {
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * kTokThreads + threadIdx.x;
+    if (t >= Tzp) return;
+    float ct = 0.0f;
+    if (t < Tv && g[t] != 0.0f) {
+        const float ratio = expf(logp[t] - old_logp[t]);  // as in the surrogate: finite and positive where g != 0
+        ct = -g[t] * ratio;
+        const int64_t y = target[t];
+        if (y >= 0 && y < V) Q[(y / kBlockK) * q_blk + t * kBlockK + y % kBlockK] = f32_to_bf16(expf(old_logp[t]) - 1.0f / ratio);
+    }
+    c[t] = ct;
+}
+
+// dst[t][:] = bf16(c[t] * src[t][:]) for t < rows_pad (c is 0 from the last valid row on: zeros).
+// One workgroup per row; H is a multiple of 64.
+template <typename T_>
+__global__ void __launch_bounds__(256)
+scale_rows_kernel(const T_ *__restrict__ src, const float *__restrict__ c, int64_t rows, int64_t H,
+                  bf16_t *__restrict__ dst) {
+    const int64_t t = blockIdx.x;
+    const float ct = c[t];
+    const bool live = t < rows && ct != 0.0f;
+    uint2 *out = reinterpret_cast<uint2 *>(dst + t * H);
+    for (int i = threadIdx.x; i < H / 4; i += 256) {
+        float x[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (live) {
+            if constexpr (sizeof(T_) == 2) {
+                const uint2 v = reinterpret_cast<const uint2 *>(src + t * H)[i];
+                x[0] = __uint_as_float(v.x << 16); x[1] = __uint_as_float(v.x & 0xffff0000u);
+                x[2] = __uint_as_float(v.y << 16); x[3] = __uint_as_float(v.y & 0xffff0000u);
+            } else {
+                const float4 v = reinterpret_cast<const float4 *>(src + t * H)[i];
+                x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+            }
+        }
+        out[i] = make_uint2(pack_bf16x2_rn(x[0] * ct, x[1] * ct), pack_bf16x2_rn(x[2] * ct, x[3] * ct));
+    }
+}
+
+// ----------------------------------------------------------------------------
 // host side
 // ----------------------------------------------------------------------------
 // The kernels use more dynamic LDS than the default limit allows.  The attribute belongs
@@ -914,10 +1045,12 @@ dz_from_logits_kernel(const uint16_t *__restrict__ Z, int64_t z_blk, const float
 // table lookup) rather than remembered in a process-wide flag.
 static int set_lds_limit() {
     hipError_t e = hipSuccess;
-    e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_sweep_kernel<false>),
+    e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_sweep_kernel<kEmitNone>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kSweepLds);
-    e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_sweep_kernel<true>),
+    e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_sweep_kernel<kEmitLogits>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kSweepLds);
+    e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(fwd_sweep_kernel<kEmitProbs>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kSweepLdsProbs);
     e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(recompute_dz_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES);
     e = e ? e : hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_store_kernel<false>),
@@ -1009,7 +1142,7 @@ int fused_fwd(const spo_pg_desc *d, float *loss, float *logp, float *lse, float 
         }
         const int64_t blocks = SweepMap(p.nTt, p.nVt).blocks();
         ScopedKernelTimer timer(kTimeFwdSweep, s);
-        fwd_sweep_kernel<false><<<static_cast<unsigned>(blocks), TL::NT, kSweepLds, s>>>(
+        fwd_sweep_kernel<kEmitNone><<<static_cast<unsigned>(blocks), TL::NT, kSweepLds, s>>>(
             W, p.Kc * 2, d->V, X, p.Kc * 2, d->T, static_cast<int>(p.Kc / kBK), p.nsplit, p.nTt, p.nVt, p.T_pad,
             p.part_max, p.part_sum, nullptr, 0, nullptr);
     }
@@ -1109,7 +1242,8 @@ template <bool KMajor>
 static void launch_gemm(const bf16_t *A, int64_t lda, int64_t M, const bf16_t *B, int64_t ldb, int64_t N, int64_t K,
                         void *out, int64_t ldo, int out_dtype, int accumulate, const int32_t *n_act, int64_t row_base,
                         int limit, const int32_t *row_map, int64_t a_blk_elems, int64_t b_blk_elems, hipStream_t s,
-                        int nsplit = 1, float *partials = nullptr, float *tail = nullptr) {
+                        int nsplit = 1, float *partials = nullptr, float *tail = nullptr,
+                        const float *row_scale = nullptr) {
     const TileOrder ord(ceil_div(M, TL::BM), ceil_div(N, TL::BN));
     const int64_t tiles = ord.nM * ord.nN, rem = tiles % kChipCUs;
     int tail_parts = 0;
@@ -1119,15 +1253,15 @@ static void launch_gemm(const bf16_t *A, int64_t lda, int64_t M, const bf16_t *B
     gemm_store_kernel<KMajor><<<static_cast<unsigned>(ord.blocks() * nsplit), TL::NT, TL::LDS_BYTES, s>>>(
         reinterpret_cast<const char *>(A), lda * 2, M, reinterpret_cast<const char *>(B), ldb * 2, N,
         static_cast<int>(K / kBK), out, ldo, out_dtype, accumulate, n_act, row_base, limit, row_map, a_blk_elems * 2,
-        b_blk_elems * 2, nsplit, partials, 0, whole, 0);
+        b_blk_elems * 2, nsplit, partials, 0, whole, 0, row_scale);
     if (nsplit > 1)
         reduce_split_kernel<<<grid1(M * (N / 4)), 256, 0, s>>>(partials, nsplit, M, N, n_act, row_base, row_map, out, ldo,
-                                                               out_dtype);
+                                                               out_dtype, row_scale);
     if (tail_parts) {
         gemm_store_kernel<KMajor><<<static_cast<unsigned>(rem * tail_parts), TL::NT, TL::LDS_BYTES, s>>>(
             reinterpret_cast<const char *>(A), lda * 2, M, reinterpret_cast<const char *>(B), ldb * 2, N,
             static_cast<int>(K / kBK), out, ldo, out_dtype, accumulate, n_act, row_base, limit, row_map, a_blk_elems * 2,
-            b_blk_elems * 2, 1, tail, whole, tiles, tail_parts);
+            b_blk_elems * 2, 1, tail, whole, tiles, tail_parts, nullptr);
         reduce_tail_kernel<<<grid1(rem * (TL::BM * TL::BN / 4)), 256, 0, s>>>(tail, tail_parts, whole, tiles, M, N,
                                                                               static_cast<float *>(out), ldo, accumulate);
     }
@@ -1243,11 +1377,14 @@ int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float g
 // factors, one pass turns the stored logits of the piece's active tokens into bf16 logit
 // gradients, and the two contractions follow: three products of size T x V x H instead of four.
 // By default a piece's stored logits stay within kDzBudgetBytes, and so do its gradients.
+// Without a loss mask the pass over the stored logits is left out as well: the sweep stores
+// bf16 scaled probabilities that the contractions read as they are (probs_reference_kernel).
 struct FbPlan {
     int64_t Tz, T_pad, V_pad, V_blk, Kc, nVt, nblk_tok;
     int nsplit;
     double *count;
-    float *g, *z_target, *part_max, *part_sum, *offs, *dW_acc, *W32, *dx_part, *dw_tail;
+    float *g, *z_target, *part_max, *part_sum, *offs, *dW_acc, *W32, *dx_part, *dw_tail, *cscale;
+    bool dense;  // no loss mask: the sweep stores what the contractions read (see probs_reference_kernel)
     FwdPartial *partials;
     int32_t *act_idx, *n_act;
     float4 *tok;
@@ -1294,7 +1431,9 @@ static FbPlan plan_fb(const spo_pg_desc *d, int64_t chunk_tokens, void *ws, bool
     p.partials = a.take<FwdPartial>(p.nblk_tok);
     p.part_max = a.take<float>(static_cast<size_t>(p.nsplit) * p.Tz);
     p.part_sum = a.take<float>(static_cast<size_t>(p.nsplit) * p.Tz);
-    p.offs = a.take<float>(static_cast<size_t>(p.nVt) * TL::WGM * p.Tz);
+    p.dense = d->mask == nullptr;
+    p.offs = a.take<float>(p.dense ? p.Tz : static_cast<size_t>(p.nVt) * TL::WGM * p.Tz);
+    p.cscale = p.dense ? a.take<float>(p.Tz) : nullptr;
     p.act_idx = a.take<int32_t>(p.Tz);
     p.n_act = a.take<int32_t>(1);
     p.tok = a.take<float4>(p.Tz);
@@ -1304,7 +1443,7 @@ static FbPlan plan_fb(const spo_pg_desc *d, int64_t chunk_tokens, void *ws, bool
     p.Xc = a.take<char>(static_cast<size_t>(p.Tz) * d->H * (d->dtype == SPO_FP32 ? 4 : 2));
     p.WT = want_dx ? a.take<bf16_t>(static_cast<size_t>(d->H) * p.V_blk) : nullptr;
     p.Z = a.take<uint16_t>(static_cast<size_t>(p.Tz) * p.V_blk);
-    p.dZ = a.take<bf16_t>(static_cast<size_t>(p.Tz) * p.V_blk);
+    p.dZ = p.dense ? nullptr : a.take<bf16_t>(static_cast<size_t>(p.Tz) * p.V_blk);
     p.Xb = p.Xs = p.Ws = p.Wvh = nullptr;
     p.dW_acc = p.W32 = nullptr;
     if (d->dtype == SPO_FP32) {
@@ -1372,7 +1511,7 @@ int fused_fwd_bwd(const spo_pg_desc *d, float grad_loss, float *loss, float *log
         target_logit_kernel<bf16_t><<<grid1(T, 4), 256, 0, s>>>(static_cast<const bf16_t *>(d->hidden), Wvh, H, V, T,
                                                                 d->target, p.z_target);
     }
-    if (d_hidden) {  // rows of tokens without a gradient stay zero
+    if (d_hidden && !p.dense) {  // rows of tokens without a gradient stay zero (without a mask every row is written)
         const int64_t words = T * H / (d_hidden_dtype == SPO_FP32 ? 1 : 2);
         fill_zero_kernel<<<grid1(words), 256, 0, s>>>(static_cast<uint32_t *>(d_hidden), words);
     }
@@ -1386,11 +1525,17 @@ int fused_fwd_bwd(const spo_pg_desc *d, float grad_loss, float *loss, float *log
             Xk = reinterpret_cast<const char *>(p.Xs);
         }
         const SweepMap map(Tzp / TL::BN, p.nVt, p.nsplit);
+        if (p.dense) probs_reference_kernel<<<grid1(Tzp, kTokThreads), kTokThreads, 0, s>>>(p.z_target + t0, d->old_logp + t0, Tv, Tzp, p.offs);
         {
             ScopedKernelTimer timer(kTimeFwdSweep, s);
-            fwd_sweep_kernel<true><<<static_cast<unsigned>(map.blocks()), TL::NT, kSweepLds, s>>>(
-                Wk, p.Kc * 2, V, Xk, p.Kc * 2, Tv, static_cast<int>(p.Kc / kBK), map.nsplit, map.nTt, map.nVt, Tzp,
-                p.part_max, p.part_sum, p.Z, Tzp * kBlockK, p.offs);
+            if (p.dense)
+                fwd_sweep_kernel<kEmitProbs><<<static_cast<unsigned>(map.blocks()), TL::NT, kSweepLdsProbs, s>>>(
+                    Wk, p.Kc * 2, V, Xk, p.Kc * 2, Tv, static_cast<int>(p.Kc / kBK), map.nsplit, map.nTt, map.nVt, Tzp,
+                    p.part_max, p.part_sum, p.Z, Tzp * kBlockK, p.offs);
+            else
+                fwd_sweep_kernel<kEmitLogits><<<static_cast<unsigned>(map.blocks()), TL::NT, kSweepLds, s>>>(
+                    Wk, p.Kc * 2, V, Xk, p.Kc * 2, Tv, static_cast<int>(p.Kc / kBK), map.nsplit, map.nTt, map.nVt, Tzp,
+                    p.part_max, p.part_sum, p.Z, Tzp * kBlockK, p.offs);
         }
         token_loss_kernel<<<grid1(Tv, kTokThreads), kTokThreads, 0, s>>>(
             p.part_max, p.part_sum, map.nsplit, Tzp, p.z_target + t0, Tv, d->old_logp + t0, d->mask ? d->mask + t0 : nullptr,
@@ -1400,6 +1545,36 @@ int fused_fwd_bwd(const spo_pg_desc *d, float grad_loss, float *loss, float *log
         grad_scale_kernel<<<grid1(Tzp, kTokThreads), kTokThreads, 0, s>>>(
             logp + t0, d->old_logp + t0, d->mask ? d->mask + t0 : nullptr, d->adv_norm, d->cu_seqlens, d->B, Tv, Tzp,
             d->eps_low, d->eps_high, grad_loss, p.count, p.g + t0, t0);
+        if (p.dense) {
+            // the contractions run on what the sweep stored: every row of the piece, scaled by c_t
+            probs_patch_kernel<<<grid1(Tzp, kTokThreads), kTokThreads, 0, s>>>(
+                p.g + t0, logp + t0, d->old_logp + t0, d->target + t0, V, Tv, Tzp, p.Z, Tzp * kBlockK, p.cscale);
+            const bf16_t *Q = p.Z;
+            if (d_hidden) {
+                ScopedKernelTimer timer(kTimeDHidden, s);
+                launch_gemm<false>(Q, kBlockK, Tv, p.WT, kBlockK, H, p.V_pad, static_cast<char *>(d_hidden) + t0 * H * dx_elt, H,
+                                   d_hidden_dtype, 0, nullptr, 0, 0, nullptr, Tzp * kBlockK, H * kBlockK, s, p.dx_split,
+                                   p.dx_part, nullptr, p.cscale);
+            }
+            if (d_W) {
+                bf16_t *Xc = d->dtype == SPO_FP32 ? p.Xb : static_cast<bf16_t *>(p.Xc);  // c_t x_t, the rows past the piece zero
+                if (d->dtype == SPO_FP32)
+                    scale_rows_kernel<float><<<static_cast<unsigned>(Tzp), 256, 0, s>>>(
+                        reinterpret_cast<const float *>(Xpiece), p.cscale, Tv, H, Xc);
+                else
+                    scale_rows_kernel<bf16_t><<<static_cast<unsigned>(Tzp), 256, 0, s>>>(
+                        reinterpret_cast<const bf16_t *>(Xpiece), p.cscale, Tv, H, Xc);
+                const int acc = (c > 0 || accumulate_dW) ? 1 : 0;
+                ScopedKernelTimer timer(kTimeDW, s);
+                if (d->w_layout == SPO_W_VH)
+                    launch_gemm<true>(Q, kBlockK, V, Xc, H, H, Tzp, dW32, H, SPO_FP32, acc, nullptr, 0, 0, nullptr,
+                                      Tzp * kBlockK, 0, s, 1, nullptr, p.dw_tail);
+                else
+                    launch_gemm<true>(Xc, H, H, Q, kBlockK, V, Tzp, dW32, V, SPO_FP32, acc, nullptr, 0, 0, nullptr, 0,
+                                      Tzp * kBlockK, s, 1, nullptr, p.dw_tail);
+            }
+            continue;
+        }
         compact_active_kernel<<<1, 1024, 0, s>>>(p.g + t0, Tv, p.act_idx, p.n_act);
         const bf16_t *Xrows;
         if (d->dtype == SPO_FP32) {

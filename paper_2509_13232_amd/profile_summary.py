@@ -119,7 +119,7 @@ def hbm_traffic(args, b):
          "Calibration: `--calibrate-copy` runs a plain elementwise copy that reads 1 GiB and writes 1 GiB (1048576 KiB",
          f"each). The counters read FETCH_SIZE = {sum(cf) / len(cf):.0f} and WRITE_SIZE = {sum(cw) / len(cw):.0f} for it, so readings are",
          f"scaled by {sf:.3f} (fetch) and {sw:.3f} (write).\n",
-         "Average per launch over all launches of a step, scaled, in GB (1e9 bytes); 'algorithmic' = operands read once +",
+         "Average per launch over all launches of the one profiled step, scaled, in GB (1e9 bytes); 'algorithmic' = operands read once +",
          "outputs written once, for the average launch:\n",
          f"    {'kernel':16s} {'launches':>8s} {'fetch GB':>10s} {'write GB':>10s} {'alg. read':>10s} {'alg. write':>11s}"]
     total = {}
@@ -127,8 +127,10 @@ def hbm_traffic(args, b):
         fv, wv = _of(f, sub), _of(w, sub)
         if not fv:
             continue
-        fb, wb = sum(fv) / len(fv) * 1024 * sf, sum(wv) / len(wv) * 1024 * sw
-        o.append(f"    {name:16s} {len(fv):8d} {fb / 1e9:10.2f} {wb / 1e9:10.2f} {alg[name][0] / 1e9:10.2f} {alg[name][1] / 1e9:11.2f}")
+        # a launch as bench.py counts it (dW's short last round of tiles is a dispatch of its own, inside the same launch)
+        nl = kern[name]["launches_per_step"] if name in kern else len(fv)
+        fb, wb = sum(fv) / nl * 1024 * sf, sum(wv) / nl * 1024 * sw
+        o.append(f"    {name:16s} {nl:8d} {fb / 1e9:10.2f} {wb / 1e9:10.2f} {alg[name][0] / 1e9:10.2f} {alg[name][1] / 1e9:11.2f}")
         total[name] = fb + wb
     o.append("\ntraffic_bytes_per_launch: " + " ".join(f"{k}={v:.4g}" for k, v in total.items()))
     o.append("\n(fetch + write; the line above is what bench.py quotes as roofline.traffic while the kernel sources and the")
@@ -156,7 +158,7 @@ def mfma_counters(args, b):
         mops, busy, gui = _of(c["SQ_INSTS_VALU_MFMA_MOPS_BF16"], sub), _of(c["SQ_VALU_MFMA_BUSY_CYCLES"], sub), _of(c["GRBM_GUI_ACTIVE"], sub)
         if not mops:
             continue
-        o.append(f"    {name:16s} {len(mops):8d} {sum(mops):12.4e} {sum(mops) * 512:16.4e} "
+        o.append(f"    {name:16s} {b['roofline']['kernels'].get(name, {}).get('launches_per_step', len(mops)):8d} {sum(mops):12.4e} {sum(mops) * 512:16.4e} "
                  f"{sum(busy) / 1024 / (sum(gui) / 8):16.3f} {sum(gui) / 8:15.4e}")
     T, H, V, ta = b["config"]["T"], b["config"]["H"], b["config"]["V"], b["active_tokens"]
     pad = lambda x, a: (x + a - 1) // a * a
