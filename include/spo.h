@@ -17,9 +17,10 @@
  *
  * One training iteration calls, in this order (training-loop algorithm of the
  * paper): spo_sample_prompts -> [rollout, outside this library] ->
- * spo_advantages -> spo_tracker_update -> spo_pg_loss_fwd / spo_pg_loss_bwd per
- * mini-batch.  spo_advantages must see the tracker BEFORE spo_tracker_update:
- * the baseline of an advantage is the pre-update estimate.
+ * spo_advantages -> spo_tracker_update -> per mini-batch spo_pg_loss_fwd /
+ * spo_pg_loss_bwd, or spo_pg_loss_fwd_bwd when the weight of the loss in the
+ * total is known beforehand.  spo_advantages must see the tracker BEFORE
+ * spo_tracker_update: the baseline of an advantage is the pre-update estimate.
  */
 #ifndef SPO_H_
 #define SPO_H_

@@ -1,11 +1,15 @@
 // Fused LM-head + clipped policy-gradient loss, forward and backward, on bf16
 // MFMA (Method, PPO-Clip objective over the full vocabulary).  The [T x V] logits
 // never exist in memory:
-//   forward   sweeps vocabulary tiles, keeping a running (max, sum-exp) per token
-//             in registers and catching the sampled token's logit on the way;
+//   forward   sweeps vocabulary tiles, keeping a running (max, sum-exp) per token;
+//             the sampled token's logit is one dot product per token beside it;
 //   backward  recomputes the logits tile by tile, turns them into bf16 logit
 //             gradients dZ for one chunk of tokens at a time, and contracts that
-//             chunk twice (dHidden = dZ W, dW += dZ^T X).
+//             chunk twice (dHidden = dZ W, dW += dZ^T X);
+//   forward and backward in one call (when d(total)/d(loss) is known up front)
+//             walks the batch in pieces: the sweep of a piece also stores, at two
+//             bytes per logit, what the two contractions of that piece then
+//             read, so the logits are formed once.
 // The logits and dHidden run through the main loop of gemm_core.hpp in the form
 // D[m][n] = sum_k A[m][k] B[n][k] (a transposition kernel provides the head with
 // the vocabulary contiguous for dHidden); dW contracts over tokens, the row index
