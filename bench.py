@@ -413,6 +413,12 @@ def main() -> int:
             r["steps"], r["warmup"] = st, wu
             others[name] = r
         out["other_workloads"] = others
+        # the same workload through the other way to the gradients (forward then backward, or the one call)
+        r, lv = run_workload(spo, wl, torch, args.workload, 3, 1, args.chunk_tokens, True, not one_call)
+        del lv
+        torch.cuda.empty_cache()
+        r["steps"], r["warmup"] = 3, 1
+        out["other_path"] = r
 
     print(json.dumps(out), flush=True)
     return 0

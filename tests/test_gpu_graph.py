@@ -21,10 +21,12 @@ def spo():
     return binding
 
 
-def test_step_replays_from_a_captured_graph(spo):
+@pytest.mark.parametrize("mask_frac", [None, 0.25], ids=["no_mask", "masked"])
+def test_step_replays_from_a_captured_graph(spo, mask_frac):
+    # both forms of the one call: without a mask the sweep stores scaled probabilities, with one logits
     cfg = wl.scaled(wl.CONFIGS["C2"], name="graph", H=256, V=3000)
     lengths = [37, 300, 1, 255, 120, 64, 200, 90]
-    case = Case(cfg, lengths, mask_frac=0.25)
+    case = Case(cfg, lengths, mask_frac=mask_frac)
     B, d = len(lengths), "cuda"
     say(f"graph capture of the step: T={case.T} H=256 V=3000 B={B} N={cfg.N}")
     a0, b0 = wl.tracker_state(cfg)
@@ -35,7 +37,7 @@ def test_step_replays_from_a_captured_graph(spo):
     hidden, W = case.hidden.to(d), case.W.to(d)
     target = torch.as_tensor(case.target).to(d)
     old = torch.as_tensor((-np.log(cfg.V) + case.noise).astype(np.float32)).to(d)
-    mask = torch.as_tensor(case.mask).to(d)
+    mask = None if case.mask is None else torch.as_tensor(case.mask).to(d)
     cu = torch.as_tensor(case.cu).to(d)
     adv_holder = torch.zeros(B, dtype=torch.float32, device=d)
     desc = spo.make_desc(hidden, W, target, old, mask, adv_holder, cu, cfg.eps_low, cfg.eps_high)
