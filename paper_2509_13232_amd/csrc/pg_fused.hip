@@ -369,9 +369,15 @@ fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const
         const float *r = offs + n0 + TL::wave_n0() + (lane & 15);
         state()[2] = make_float4(r[0], r[TL::MI], r[2 * TL::MI], r[3 * TL::MI]);
     }
-    // online log-sum-exp over the rows of one finished tile: three operations per logit
-    // (multiply-add into the exponent, exponential, add) plus its share of the maximum
-    auto reduce = [&](TL::Acc &acc, int64_t m0) {
+    // One finished tile.  Online log-sum-exp over its rows: three operations per logit (multiply-add
+    // into the exponent, exponential, add) plus its share of the maximum.  With Emit, the tile's
+    // values also leave for memory, token column by token column as each is done, so that the stores
+    // of one column are on their way while the next is being worked on.  A lane holds runs of four
+    // consecutive vocabulary entries of one token; after an exchange between neighbouring lane
+    // groups it holds 16 contiguous bytes of two 64-entry blocks out of four (the scheme of the
+    // recompute's epilogue below).
+    auto finish_tile = [&](TL::Acc &acc, int64_t vt) {
+        const int64_t m0 = vt * TL::BM;
         if (m0 + TL::BM > V) {  // ragged last tile: rows past the vocabulary do not count
 #pragma unroll
             for (int fm = 0; fm < TL::FM; ++fm)
@@ -381,9 +387,19 @@ fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const
 #pragma unroll
                         for (int fn = 0; fn < TL::FN; ++fn) acc[fm][fn][r] = -INFINITY;
         }
+        int l = threadIdx.x & 63;
+        asm volatile("" : "+v"(l));  // not to be traced: nothing derived from it lives through the main loop
+        const int grp = l >> 4, col = l & 15;
+        const int64_t wave_blk = vt * (TL::BM / kBlockK) + TL::wave_m0() / kBlockK;
+        const int piece = (grp & 1) * 16 + (grp & 2) * 4;  // elements: byte offset 32 * (g & 1) + 8 * (g & 2)
         float4 *st = state();
         const float4 m4 = st[0], s4 = st[1];
         float m_run[TL::FN] = {m4.x, m4.y, m4.z, m4.w}, s_run[TL::FN] = {s4.x, s4.y, s4.z, s4.w};
+        float ref[TL::FN] = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (Emit == kEmitProbs) {
+            const float4 r4 = st[2];
+            ref[0] = r4.x; ref[1] = r4.y; ref[2] = r4.z; ref[3] = r4.w;
+        }
 #pragma unroll
         for (int fn = 0; fn < TL::FN; ++fn) {
             float mx = -INFINITY;
@@ -395,100 +411,62 @@ fwd_sweep_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V, const
             // row of the tile is masked (their logits are -inf and add exact zeros)
             const float nm = fmaxf(m_run[fn], mx);
             const float c = -nm * kLog2e;
+            // what is stored of an entry: a * value + b, with value the exponential (kEmitProbs: times
+            // exp(nm - r), capped) or the logit itself (kEmitLogits: minus the offset, the largest logit the
+            // wavefront's 128 rows have shown for this token so far)
+            float a = 0.0f, off = 0.0f;
+            if (Emit == kEmitProbs) a = __builtin_amdgcn_exp2f(fminf(fmaf(nm, kLog2e, -ref[fn]), 126.0f));
+            if (Emit == kEmitLogits) {
+                off = fmaxf(nm, __shfl_xor(nm, 16, kWave));
+                off = fmaxf(off, __shfl_xor(off, 32, kWave));
+                if (grp == 0)
+                    offs[(vt * TL::WGM + TL::wave_m0() / TL::WM) * T_pad + n0 + TL::wave_n0() + fn * TL::MI + col] = off;
+            }
             float s = 0.0f;
+            uint16_t *row = Emit ? Z + (n0 + TL::wave_n0() + fn * TL::MI + col) * kBlockK + piece : nullptr;
 #pragma unroll
-            for (int fm = 0; fm < TL::FM; ++fm)
+            for (int b = 0; b < TL::FM / 4; ++b) {
+                uint32_t lo[4], hi[4];
 #pragma unroll
-                for (int r = 0; r < TL::ACC_R; ++r) {
-                    const float e = __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r], kLog2e, c));
-                    s += e;
-                    if (Emit == kEmitProbs) acc[fm][fn][r] = e;  // exp(logit - nm), rescaled to the reference by emit_probs
+                for (int q = 0; q < 4; ++q) {
+                    float e[4], v[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        e[r] = __builtin_amdgcn_exp2f(fmaf(acc[4 * b + q][fn][r], kLog2e, c));
+                        s += e[r];
+                        v[r] = Emit == kEmitProbs ? e[r] * a : acc[4 * b + q][fn][r] - off;
+                    }
+                    if (Emit == kEmitProbs) {
+                        lo[q] = pack_bf16x2_rn(v[0], v[1]);
+                        hi[q] = pack_bf16x2_rn(v[2], v[3]);
+                    }
+                    if (Emit == kEmitLogits) {
+                        lo[q] = pack_f16x2_rn(v[0], v[1]);
+                        hi[q] = pack_f16x2_rn(v[2], v[3]);
+                    }
                 }
+                if (Emit) {
+                    swap_lane_groups(lo[0], lo[1]);
+                    swap_lane_groups(hi[0], hi[1]);
+                    swap_lane_groups(lo[2], lo[3]);
+                    swap_lane_groups(hi[2], hi[3]);
+                    uint16_t *out = row + (wave_blk + b) * z_blk;
+                    *reinterpret_cast<uint4 *>(out) = make_uint4(lo[0], hi[0], lo[1], hi[1]);
+                    *reinterpret_cast<uint4 *>(out + kBlockK / 2) = make_uint4(lo[2], hi[2], lo[3], hi[3]);
+                }
+            }
             s_run[fn] = s_run[fn] * __builtin_amdgcn_exp2f((m_run[fn] - nm) * kLog2e) + s;
             m_run[fn] = nm;
         }
         st[0] = make_float4(m_run[0], m_run[1], m_run[2], m_run[3]);
         st[1] = make_float4(s_run[0], s_run[1], s_run[2], s_run[3]);
     };
-    // Emit: the finished tile (rows past the vocabulary already -inf) as fp16 offsets.  A lane
-    // holds runs of four consecutive vocabulary entries of one token; after an exchange between
-    // neighbouring lane groups it holds 16 contiguous bytes of two 64-entry blocks out of four
-    // (the scheme of the recompute's epilogue below).
-    auto emit = [&](TL::Acc &acc, int64_t vt) {
-        int l = threadIdx.x & 63;
-        asm volatile("" : "+v"(l));  // not to be traced: nothing derived from it lives through the main loop
-        const int grp = l >> 4, col = l & 15;
-        const float4 m4 = state()[0];  // this lane's running maxima, the finished tile included
-        float off[TL::FN] = {m4.x, m4.y, m4.z, m4.w};
-#pragma unroll
-        for (int fn = 0; fn < TL::FN; ++fn) {  // over the four lane groups: all 128 rows of the wavefront
-            off[fn] = fmaxf(off[fn], __shfl_xor(off[fn], 16, kWave));
-            off[fn] = fmaxf(off[fn], __shfl_xor(off[fn], 32, kWave));
-            if (grp == 0)
-                offs[(vt * TL::WGM + TL::wave_m0() / TL::WM) * T_pad + n0 + TL::wave_n0() + fn * TL::MI + col] = off[fn];
-        }
-        const int64_t wave_blk = vt * (TL::BM / kBlockK) + TL::wave_m0() / kBlockK;
-        const int piece = (grp & 1) * 16 + (grp & 2) * 4;  // elements: byte offset 32 * (g & 1) + 8 * (g & 2)
-#pragma unroll
-        for (int fn = 0; fn < TL::FN; ++fn) {
-            uint16_t *row = Z + (n0 + TL::wave_n0() + fn * TL::MI + col) * kBlockK + piece;
-#pragma unroll
-            for (int b = 0; b < TL::FM / 4; ++b) {
-                uint32_t lo[4], hi[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    lo[q] = pack_f16x2_rn(acc[4 * b + q][fn][0] - off[fn], acc[4 * b + q][fn][1] - off[fn]);
-                    hi[q] = pack_f16x2_rn(acc[4 * b + q][fn][2] - off[fn], acc[4 * b + q][fn][3] - off[fn]);
-                }
-                swap_lane_groups(lo[0], lo[1]);
-                swap_lane_groups(hi[0], hi[1]);
-                swap_lane_groups(lo[2], lo[3]);
-                swap_lane_groups(hi[2], hi[3]);
-                uint16_t *out = row + (wave_blk + b) * z_blk;
-                *reinterpret_cast<uint4 *>(out) = make_uint4(lo[0], hi[0], lo[1], hi[1]);
-                *reinterpret_cast<uint4 *>(out + kBlockK / 2) = make_uint4(lo[2], hi[2], lo[3], hi[3]);
-            }
-        }
-    };
-    // kEmitProbs: acc holds exp(logit - m) with m this lane's running maximum (reduce left it there)
-    auto emit_probs = [&](TL::Acc &acc, int64_t vt) {
-        int l = threadIdx.x & 63;
-        asm volatile("" : "+v"(l));
-        const int grp = l >> 4, col = l & 15;
-        const float4 m4 = state()[0], r4 = state()[2];
-        const float m[TL::FN] = {m4.x, m4.y, m4.z, m4.w}, ref[TL::FN] = {r4.x, r4.y, r4.z, r4.w};
-        const int64_t wave_blk = vt * (TL::BM / kBlockK) + TL::wave_m0() / kBlockK;
-        const int piece = (grp & 1) * 16 + (grp & 2) * 4;
-#pragma unroll
-        for (int fn = 0; fn < TL::FN; ++fn) {
-            const float f = __builtin_amdgcn_exp2f(fminf(fmaf(m[fn], kLog2e, -ref[fn]), 126.0f));  // exp(m - r)
-            uint16_t *row = Z + (n0 + TL::wave_n0() + fn * TL::MI + col) * kBlockK + piece;
-#pragma unroll
-            for (int b = 0; b < TL::FM / 4; ++b) {
-                uint32_t lo[4], hi[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    lo[q] = pack_bf16x2_rn(acc[4 * b + q][fn][0] * f, acc[4 * b + q][fn][1] * f);
-                    hi[q] = pack_bf16x2_rn(acc[4 * b + q][fn][2] * f, acc[4 * b + q][fn][3] * f);
-                }
-                swap_lane_groups(lo[0], lo[1]);
-                swap_lane_groups(hi[0], hi[1]);
-                swap_lane_groups(lo[2], lo[3]);
-                swap_lane_groups(hi[2], hi[3]);
-                uint16_t *out = row + (wave_blk + b) * z_blk;
-                *reinterpret_cast<uint4 *>(out) = make_uint4(lo[0], hi[0], lo[1], hi[1]);
-                *reinterpret_cast<uint4 *>(out + kBlockK / 2) = make_uint4(lo[2], hi[2], lo[3], hi[3]);
-            }
-        }
-    };
     auto tile_ops = [&](int64_t vt) { return typename TL::Operands{W, ldw_bytes, vt * TL::BM, V, X, ldx_bytes, n0, T, 0, 0}; };
     for (int64_t vt = vt0; vt < vt1; ++vt) {
         TL::Acc acc;
         TL::zero(acc);
         TL::mainloop(tile_ops(vt), KT, lds, acc);
-        reduce(acc, vt * TL::BM);
-        if (Emit == kEmitLogits) emit(acc, vt);
-        if (Emit == kEmitProbs) emit_probs(acc, vt);
+        finish_tile(acc, vt);
     }
     // merge the lane groups that hold different rows of the same token, then the WGM
     // wavefronts that share a token column
