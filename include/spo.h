@@ -314,7 +314,10 @@ int spo_pg_loss_bwd(const spo_pg_desc *d, const float *logp, const float *lse, f
  *    c_t = -g_t * ratio_t.  After the sweep one entry per token is rewritten and the
  *    contractions read q as it is: d_hidden_t = c_t * (q_t W), d_W = q^T (c X).
  *    Every token of the piece is multiplied, also those whose factor is zero (the
- *    clipped ones); exponents are capped so that nothing stored is infinite.
+ *    clipped ones); exponents are capped so that nothing stored is infinite.  c_t
+ *    grows with the square of the ratio: an unclipped token whose ratio exceeds
+ *    about e^40 overflows it (spo_pg_loss_bwd, whose factor is linear in the ratio,
+ *    reaches e^80).
  *  - mask != NULL: fp16 of the logit minus an offset per (token, 128 vocabulary
  *    entries), the largest logit the sweep has met for that token up to there.  An
  *    entry within d of its row's largest logit is stored within d of zero, where
