@@ -335,7 +335,7 @@ struct Tile {
     };
 
     // acc += sum_k A[k][m0..] * B[k][n0..] over k < kBK*KT; every row k < kBK*KT of both operands
-    // must be readable.  Same schedule as mainloop16; the fragments come out of LDS with
+    // must be readable.  Same schedule as mainloop; the fragments come out of LDS with
     // ds_read_b64_tr_b16: within a group of 16 lanes, lane i receives element i%4 of the four
     // source lanes i/4, i/4+4, i/4+8, i/4+12.  Source lane s points at row k0 + s/4, columns
     // 4*(s%4).. of a 16-column block, so lane i ends up with rows k0..k0+3 of column i; the
@@ -406,7 +406,7 @@ struct Tile {
         fence_barrier();
 #pragma unroll
         for (int r = 0; r < NR; ++r) read_half(0, 0, r);
-        auto step = [&](int kt, auto more_t, auto feed_t) {  // flags as in mainloop16
+        auto step = [&](int kt, auto more_t, auto feed_t) {  // flags as in mainloop
             constexpr bool MORE = decltype(more_t)::value, FEED = decltype(feed_t)::value;
             // ---- slice 0 of stage kt, reading its slice 1 between the MFMAs
 #pragma unroll

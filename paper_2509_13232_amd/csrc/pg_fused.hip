@@ -39,6 +39,7 @@ constexpr int kSweepSplits = 16;  // vocabulary splits of the forward sweep on l
 // at H = 4096, V = 151936 the step takes about 1 % longer with 8 GiB than with 40 GB.
 constexpr int64_t kDzBudgetBytes = int64_t(8) << 30;
 constexpr int kChipCUs = 256;
+constexpr int kTailTiles = kChipCUs;  // fp32 tiles of room for the parts of dW's last round of tiles (see launch_gemm)
 
 static int64_t gcd64(int64_t a, int64_t b) { return b ? gcd64(b, a % b) : a; }
 
@@ -1195,7 +1196,7 @@ static BwdPlan plan_bwd(const spo_pg_desc *d, int64_t chunk_tokens, void *ws, bo
         p.Wvh = a.take<bf16_t>(static_cast<size_t>(d->V) * d->H);
     }
     if (need_dw_acc) p.dW_acc = a.take<float>(static_cast<size_t>(d->V) * d->H);
-    p.dw_tail = a.take<float>(static_cast<size_t>(kChipCUs) * TL::BM * TL::BN);
+    p.dw_tail = a.take<float>(static_cast<size_t>(kTailTiles) * TL::BM * TL::BN);
     p.bytes = a.used;
     return p;
 }
@@ -1218,8 +1219,6 @@ static void launch_transpose(const SrcT *src, int64_t R, int64_t C, int64_t ld_s
 // count is known here) a short last round is launched on its own, every tile cut along the
 // contraction into as many parts as fill the chip, and reduce_tail_kernel adds the parts in
 // order: 9504 tiles on 256 units take 37 rounds and an eighth instead of 38.
-constexpr int kTailTiles = kChipCUs;
-
 template <bool KMajor>
 static void launch_gemm(const bf16_t *A, int64_t lda, int64_t M, const bf16_t *B, int64_t ldb, int64_t N, int64_t K,
                         void *out, int64_t ldo, int out_dtype, int accumulate, const int32_t *n_act, int64_t row_base,
@@ -1437,7 +1436,7 @@ static FbPlan plan_fb(const spo_pg_desc *d, int64_t chunk_tokens, void *ws, bool
         p.Wvh = a.take<bf16_t>(static_cast<size_t>(d->V) * d->H);
     }
     if (need_dw_acc) p.dW_acc = a.take<float>(static_cast<size_t>(d->V) * d->H);
-    p.dw_tail = a.take<float>(static_cast<size_t>(kChipCUs) * TL::BM * TL::BN);
+    p.dw_tail = a.take<float>(static_cast<size_t>(kTailTiles) * TL::BM * TL::BN);
     p.bytes = a.used;
     return p;
 }
