@@ -39,7 +39,7 @@ constexpr int kSweepSplits = 16;  // vocabulary splits of the forward sweep on l
 // at H = 4096, V = 151936 the step takes about 1 % longer with 8 GiB than with 40 GB.
 constexpr int64_t kDzBudgetBytes = int64_t(8) << 30;
 constexpr int kChipCUs = 256;
-constexpr int kTailTiles = kChipCUs;  // fp32 tiles of room for the parts of dW's last round of tiles (see launch_gemm)
+constexpr int kTailTiles = kChipCUs;  // fp32 tiles of room for the parts of a short last round of tiles (see TailCut)
 
 static int64_t gcd64(int64_t a, int64_t b) { return b ? gcd64(b, a % b) : a; }
 
@@ -629,6 +629,25 @@ recompute_dz_kernel(const char *__restrict__ W, int64_t ldw_bytes, int64_t V,
     }
 }
 
+// A launch ends in a partly filled round of tiles when its tile count is no multiple of the chip's
+// compute units.  A short last round (at most half of the units busy) is cut off: the tiles
+// before it run as they are, in whole rounds, and the `rem` tiles after them are each cut along the
+// contraction into `parts` runs whose partial results are added in a fixed order afterwards.  Host
+// and device code ask the same function, so the number of tiles may be known on the device only.
+struct TailCut {
+    int64_t whole;  // tiles that run in whole rounds (all of them when nothing is cut)
+    int rem, parts;
+    __host__ __device__ explicit TailCut(int64_t tiles) : whole(tiles), rem(0), parts(1) {
+        const int r = static_cast<int>(tiles % kChipCUs);
+        if (tiles > kChipCUs && r > 0 && r <= kChipCUs / 2) {
+            whole = tiles - r;
+            rem = r;
+            parts = kChipCUs / r < 8 ? kChipCUs / r : 8;
+        }
+    }
+};
+constexpr int kTailNone = 0, kTailWhole = 1, kTailCut = 2;  // what a launch does about a short last round
+
 // ----------------------------------------------------------------------------
 // backward, steps 2 and 3: plain contraction with a store / accumulate epilogue
 // ----------------------------------------------------------------------------
@@ -664,19 +683,23 @@ gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, cons
                   int64_t ldb_bytes, int64_t N, int KT, void *__restrict__ out, int64_t ldo, int out_dtype,
                   int accumulate, const int32_t *__restrict__ n_act, int64_t row_base, int limit,
                   const int32_t *__restrict__ row_map, int64_t a_blk, int64_t b_blk, int nsplit,
-                  float *__restrict__ partials, int64_t tile_lo, int64_t tile_hi, int tail_parts,
-                  const float *__restrict__ row_scale) {
+                  float *__restrict__ partials, int tail, const float *__restrict__ row_scale) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     constexpr int bpt = TL::BM / kBlockK;  // blocks per tile edge
     static_assert(TL::BM % kBlockK == 0 && TL::BN == TL::BM, "a tile of a blocked operand is a whole number of blocks");
     static_assert(TL::WGM == 2 && TL::BN * 4 * (TL::BM / 2) <= TL::LDS_BYTES, "half a tile of fp32 fits the operand stages");
     const int64_t tiles_n = ceil_div(N, TL::BN);
+    int64_t m_end = M;
+    if (n_act && limit == kLimitRows) m_end = active_rows(n_act, row_base, M);
+    // kTailWhole: the launch of the whole rounds; kTailCut: the launch of the cut tiles (workgroup
+    // i * parts + p takes part p of tile whole + i of the row-major order); both see the same cut
+    const TailCut cut(tail == kTailNone ? 0 : ceil_div(m_end, TL::BM) * tiles_n);
     int64_t tm, tn;
     int part;
-    if (tail_parts > 0) {  // tile tile_lo + i of the row-major order, part p: workgroup i * tail_parts + p
-        part = static_cast<int>(blockIdx.x % tail_parts);
-        const int64_t t = tile_lo + blockIdx.x / tail_parts;
-        if (t >= tile_hi) return;
+    if (tail == kTailCut) {
+        if (blockIdx.x >= static_cast<unsigned>(cut.rem * cut.parts)) return;
+        part = static_cast<int>(blockIdx.x % cut.parts);
+        const int64_t t = cut.whole + blockIdx.x / cut.parts;
         tm = t / tiles_n;
         tn = t % tiles_n;
     } else {
@@ -684,21 +707,17 @@ gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, cons
         const int64_t per_part = ord.blocks();
         part = static_cast<int>(blockIdx.x / per_part);
         if (!ord.tile(blockIdx.x % per_part, tm, tn)) return;
-        if (tm * tiles_n + tn >= tile_hi) return;  // left to the launch that cuts the last tiles along the contraction
+        if (tail == kTailWhole && tm * tiles_n + tn >= cut.whole) return;  // left to the launch of the cut tiles
     }
     const int64_t m0 = tm * TL::BM, n0 = tn * TL::BN;
-    int64_t m_end = M;
-    if (n_act && limit == kLimitRows) {
-        m_end = active_rows(n_act, row_base, M);
-        if (m0 >= m_end) return;
-    }
+    if (m0 >= m_end) return;
     if (n_act && limit == kLimitK) {
         const int64_t k_rows = active_rows(n_act, row_base, static_cast<int64_t>(KT) * kBK);
         KT = __builtin_amdgcn_readfirstlane(static_cast<int>(ceil_div(k_rows, TL::BN) * (TL::BN / kBK)));
-        if (KT == 0 && accumulate && !tail_parts) return;  // nothing to add
+        if (KT == 0 && accumulate && tail != kTailCut) return;  // nothing to add
     }
     int kt0 = 0;
-    const int parts = tail_parts > 0 ? tail_parts : nsplit;
+    const int parts = tail == kTailCut ? cut.parts : nsplit;
     if (parts > 1) {  // this part's run of k-steps
         const int per = (KT + parts - 1) / parts;
         kt0 = part * per;
@@ -729,8 +748,8 @@ gemm_store_kernel(const char *__restrict__ A, int64_t lda_bytes, int64_t M, cons
         accumulate = 0;
         row_map = nullptr;
     }
-    if (tail_parts > 0) {  // partial results [part][tile - tile_lo][BM][BN]
-        out = partials + (static_cast<int64_t>(part) * (tile_hi - tile_lo) + (tm * tiles_n + tn - tile_lo)) * (TL::BM * TL::BN);
+    if (tail == kTailCut) {  // partial results [part][tile - whole][BM][BN]
+        out = partials + (static_cast<int64_t>(part) * cut.rem + (tm * tiles_n + tn - cut.whole)) * (TL::BM * TL::BN);
         ldo = TL::BN;
         out_dtype = SPO_FP32;
         accumulate = 0;
@@ -855,38 +874,60 @@ reduce_split_kernel(const float *__restrict__ partials, int nsplit, int64_t M, i
     }
 }
 
-// The last, partly filled round of tiles of a launch, cut along the contraction (see launch_gemm):
-// out[m][n] (=|+=) the sum, in order, of partials[part][tile - tile_lo][m % BM][n % BN] over the
-// parts, for the tiles tile_lo <= tile < tile_hi of the row-major tile order.  Four values per thread.
+// The cut tiles of a launch's short last round (TailCut): out[row_map[m]][n] (=|+=) row_scale[m] times
+// the sum, in order, of partials[part][tile - whole][m % BM][n % BN] over the parts.  The launch is
+// sized for the most tiles a cut can have; n_act (with limit == kLimitRows), row_map and row_scale
+// may be NULL.  Four values per thread.
 __global__ void __launch_bounds__(256)
-reduce_tail_kernel(const float *__restrict__ partials, int parts, int64_t tile_lo, int64_t tile_hi, int64_t M, int64_t N,
-                   float *__restrict__ out, int64_t ldo, int accumulate) {
+reduce_tail_kernel(const float *__restrict__ partials, int64_t M, int64_t N, const int32_t *__restrict__ n_act,
+                   int64_t row_base, int limit, const int32_t *__restrict__ row_map, void *__restrict__ out, int64_t ldo,
+                   int out_dtype, int accumulate, const float *__restrict__ row_scale) {
     constexpr int64_t per_tile = TL::BM * TL::BN / 4;
+    const int64_t m_end = n_act && limit == kLimitRows ? active_rows(n_act, row_base, M) : M;
+    const int64_t tiles_n = ceil_div(N, TL::BN);
+    const TailCut cut(ceil_div(m_end, TL::BM) * tiles_n);
     const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
     const int64_t tl = i / per_tile, r = (i % per_tile) / (TL::BN / 4), c = (i % (TL::BN / 4)) * 4;
-    const int64_t t = tile_lo + tl, tiles_n = ceil_div(N, TL::BN);
-    if (t >= tile_hi) return;
+    if (tl >= cut.rem) return;
+    const int64_t t = cut.whole + tl;
     const int64_t m = (t / tiles_n) * TL::BM + r, n = (t % tiles_n) * TL::BN + c;
-    if (m >= M || n >= N) return;
+    if (m >= m_end || n >= N) return;
     float4 sum = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-    for (int p = 0; p < parts; ++p) {
+    for (int p = 0; p < cut.parts; ++p) {
         const float4 v = *reinterpret_cast<const float4 *>(
-            partials + ((static_cast<int64_t>(p) * (tile_hi - tile_lo) + tl) * TL::BM + r) * TL::BN + c);
+            partials + ((static_cast<int64_t>(p) * cut.rem + tl) * TL::BM + r) * TL::BN + c);
         sum = make_float4(sum.x + v.x, sum.y + v.y, sum.z + v.z, sum.w + v.w);
     }
-    float *o = out + m * ldo + n;
+    if (row_scale) {
+        const float sc = row_scale[m];
+        sum = make_float4(sum.x * sc, sum.y * sc, sum.z * sc, sum.w * sc);
+    }
+    const int64_t mo = row_map ? row_map[m] : m;
     const float e[4] = {sum.x, sum.y, sum.z, sum.w};
-    if (ldo % 4 == 0 && n + 3 < N && reinterpret_cast<uintptr_t>(out) % 16 == 0) {
-        float4 w = sum;
-        if (accumulate) {
-            const float4 old = *reinterpret_cast<const float4 *>(o);
-            w = make_float4(old.x + sum.x, old.y + sum.y, old.z + sum.z, old.w + sum.w);
-        }
-        *reinterpret_cast<float4 *>(o) = w;
-    } else {
+    const bool vec = ldo % 4 == 0 && n + 3 < N && reinterpret_cast<uintptr_t>(out) % 16 == 0;
+    if (out_dtype == SPO_FP32) {
+        float *o = static_cast<float *>(out) + mo * ldo + n;
+        if (vec) {
+            float4 w = sum;
+            if (accumulate) {
+                const float4 old = *reinterpret_cast<const float4 *>(o);
+                w = make_float4(old.x + sum.x, old.y + sum.y, old.z + sum.z, old.w + sum.w);
+            }
+            *reinterpret_cast<float4 *>(o) = w;
+        } else {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (n + j < N) o[j] = accumulate ? o[j] + e[j] : e[j];
+            for (int j = 0; j < 4; ++j)
+                if (n + j < N) o[j] = accumulate ? o[j] + e[j] : e[j];
+        }
+    } else {  // bf16 outputs are never added to
+        bf16_t *o = static_cast<bf16_t *>(out) + mo * ldo + n;
+        if (vec) {
+            *reinterpret_cast<uint2 *>(o) = make_uint2(pack_bf16x2_rn(e[0], e[1]), pack_bf16x2_rn(e[2], e[3]));
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (n + j < N) o[j] = f32_to_bf16(e[j]);
+        }
     }
 }
 
@@ -1156,7 +1197,7 @@ struct BwdPlan {
     float4 *tok;               // per-chunk records (g, -lse*log2e, target) of the gathered rows
     int dx_split;              // parts the dHidden contraction is cut into (1: not split)
     float *dx_part;            // their fp32 partial results [dx_split][Tc][H]
-    float *dw_tail;            // partial tiles of dW's last round (see launch_gemm)
+    float *dw_tail;            // partial tiles of a contraction's short last round (see launch_gemm)
     void *Xc;
     size_t bytes;
 };
@@ -1214,11 +1255,11 @@ static void launch_transpose(const SrcT *src, int64_t R, int64_t C, int64_t ld_s
                                                                                          R_pad, C_pad, ld_dst);
 }
 
-// A launch ends in a partly filled round of tiles when the tile count is no multiple of the
-// chip's compute units.  With `tail` (room for kTailTiles fp32 tiles; KMajor only, where the tile
-// count is known here) a short last round is launched on its own, every tile cut along the
-// contraction into as many parts as fill the chip, and reduce_tail_kernel adds the parts in
-// order: 9504 tiles on 256 units take 37 rounds and an eighth instead of 38.
+// `tail`: room for kTailTiles fp32 tiles; with it a short last round of tiles is cut along the
+// contraction (TailCut): 9504 tiles of dW on 256 units take 37 rounds and an eighth instead of 38,
+// and a dHidden launch whose number of active rows leaves a round nearly empty loses a fifth of a
+// round instead of a whole one.  Where the tile count depends on n_act the two extra launches
+// are made in any case and find out on the device that there is nothing to cut.
 template <bool KMajor>
 static void launch_gemm(const bf16_t *A, int64_t lda, int64_t M, const bf16_t *B, int64_t ldb, int64_t N, int64_t K,
                         void *out, int64_t ldo, int out_dtype, int accumulate, const int32_t *n_act, int64_t row_base,
@@ -1226,25 +1267,23 @@ static void launch_gemm(const bf16_t *A, int64_t lda, int64_t M, const bf16_t *B
                         int nsplit = 1, float *partials = nullptr, float *tail = nullptr,
                         const float *row_scale = nullptr) {
     const TileOrder ord(ceil_div(M, TL::BM), ceil_div(N, TL::BN));
-    const int64_t tiles = ord.nM * ord.nN, rem = tiles % kChipCUs;
-    int tail_parts = 0;
-    if (KMajor && tail && out_dtype == SPO_FP32 && tiles > kChipCUs && rem > 0 && rem <= kChipCUs / 4)
-        tail_parts = static_cast<int>(std::min<int64_t>(8, kChipCUs / rem));
-    const int64_t whole = tail_parts ? tiles - rem : tiles;
+    const bool rows_on_device = n_act && limit == kLimitRows;
+    const bool cut = tail && nsplit == 1 && (rows_on_device ? ord.nM * ord.nN > kChipCUs : TailCut(ord.nM * ord.nN).rem > 0);
     gemm_store_kernel<KMajor><<<static_cast<unsigned>(ord.blocks() * nsplit), TL::NT, TL::LDS_BYTES, s>>>(
         reinterpret_cast<const char *>(A), lda * 2, M, reinterpret_cast<const char *>(B), ldb * 2, N,
         static_cast<int>(K / kBK), out, ldo, out_dtype, accumulate, n_act, row_base, limit, row_map, a_blk_elems * 2,
-        b_blk_elems * 2, nsplit, partials, 0, whole, 0, row_scale);
+        b_blk_elems * 2, nsplit, partials, cut ? kTailWhole : kTailNone, row_scale);
     if (nsplit > 1)
         reduce_split_kernel<<<grid1(M * (N / 4)), 256, 0, s>>>(partials, nsplit, M, N, n_act, row_base, row_map, out, ldo,
                                                                out_dtype, row_scale);
-    if (tail_parts) {
-        gemm_store_kernel<KMajor><<<static_cast<unsigned>(rem * tail_parts), TL::NT, TL::LDS_BYTES, s>>>(
+    if (cut) {
+        // sized for the most a cut can be: half of the units' worth of tiles, as many part-tiles as units
+        gemm_store_kernel<KMajor><<<kChipCUs, TL::NT, TL::LDS_BYTES, s>>>(
             reinterpret_cast<const char *>(A), lda * 2, M, reinterpret_cast<const char *>(B), ldb * 2, N,
             static_cast<int>(K / kBK), out, ldo, out_dtype, accumulate, n_act, row_base, limit, row_map, a_blk_elems * 2,
-            b_blk_elems * 2, 1, tail, whole, tiles, tail_parts, nullptr);
-        reduce_tail_kernel<<<grid1(rem * (TL::BM * TL::BN / 4)), 256, 0, s>>>(tail, tail_parts, whole, tiles, M, N,
-                                                                              static_cast<float *>(out), ldo, accumulate);
+            b_blk_elems * 2, 1, tail, kTailCut, nullptr);
+        reduce_tail_kernel<<<grid1((kChipCUs / 2) * (TL::BM * TL::BN / 4)), 256, 0, s>>>(
+            tail, M, N, n_act, row_base, limit, row_map, out, ldo, out_dtype, accumulate, row_scale);
     }
 }
 
@@ -1331,7 +1370,7 @@ int fused_bwd(const spo_pg_desc *d, const float *logp, const float *lse, float g
             ScopedKernelTimer timer(kTimeDHidden, s);
             // both operands k-blocked over the vocabulary: a stage of a tile is 32 KiB contiguous
             launch_gemm<false>(p.dZ, kBlockK, Tcp, p.WT, kBlockK, H, p.V_pad, d_hidden, H, d_hidden_dtype, 0, p.n_act, t0,
-                               kLimitRows, p.act_idx + t0, Tcp * kBlockK, H * kBlockK, s, p.dx_split, p.dx_part);
+                               kLimitRows, p.act_idx + t0, Tcp * kBlockK, H * kBlockK, s, p.dx_split, p.dx_part, p.dw_tail);
         }
         if (d_W) {
             const int acc = (c > 0 || accumulate_dW) ? 1 : 0;
@@ -1535,7 +1574,7 @@ int fused_fwd_bwd(const spo_pg_desc *d, float grad_loss, float *loss, float *log
                 ScopedKernelTimer timer(kTimeDHidden, s);
                 launch_gemm<false>(Q, kBlockK, Tv, p.WT, kBlockK, H, p.V_pad, static_cast<char *>(d_hidden) + t0 * H * dx_elt, H,
                                    d_hidden_dtype, 0, nullptr, 0, 0, nullptr, Tzp * kBlockK, H * kBlockK, s, p.dx_split,
-                                   p.dx_part, nullptr, p.cscale);
+                                   p.dx_part, p.dw_tail, p.cscale);
             }
             if (d_W) {
                 bf16_t *Xc = d->dtype == SPO_FP32 ? p.Xb : static_cast<bf16_t *>(p.Xc);  // c_t x_t, the rows past the piece zero
@@ -1584,7 +1623,7 @@ int fused_fwd_bwd(const spo_pg_desc *d, float grad_loss, float *loss, float *log
             ScopedKernelTimer timer(kTimeDHidden, s);
             launch_gemm<false>(p.dZ, kBlockK, Tzp, p.WT, kBlockK, H, p.V_pad, static_cast<char *>(d_hidden) + t0 * H * dx_elt, H,
                                d_hidden_dtype, 0, p.n_act, 0, kLimitRows, p.act_idx, Tzp * kBlockK, H * kBlockK, s,
-                               p.dx_split, p.dx_part);
+                               p.dx_split, p.dx_part, p.dw_tail);
         }
         if (d_W) {
             const int acc = (c > 0 || accumulate_dW) ? 1 : 0;

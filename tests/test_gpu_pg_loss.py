@@ -192,6 +192,33 @@ def test_last_round_of_dW_tiles_cut_along_the_tokens(spo, oracle, w_layout, chun
     assert rel_l2(got[tail], rb["d_W"][tail]) < 2 * GRAD_TOL
 
 
+@pytest.mark.parametrize("mask_frac", [None, 0.02], ids=["no_mask", "masked"])
+def test_last_round_of_dHidden_tiles_cut_along_the_vocabulary(spo, oracle, mask_frac, one_call):
+    # ~8300 rows x 2048 hidden units: 33 x 8 = 264 tiles of d_hidden on 256 compute units, so the 8 tiles
+    # of the last round (the last 52 tokens) are cut into 8 runs of the vocabulary (9 k-steps: five parts
+    # have work).  Without a mask the one call knows the tile count on the host; otherwise the number of
+    # active tokens, and with it whether and where to cut, is known on the device only.
+    # (token counts chosen so that the rows the contraction runs over, all tokens or the ~97-99 % with a
+    # gradient, fall into the 33rd row tile)
+    T = 8300 if (one_call and mask_frac is None) else 8400 if mask_frac is None else 8560
+    say(f"fused bf16 T={T} H=2048 V=520 mask={mask_frac} one_call={one_call}: d_hidden tail tiles")
+    cfg = wl.scaled(MID, name="dxtail", H=2048, V=520)
+    case = Case(cfg, [4000, T - 4000], mask_frac=mask_frac)
+    case.set_old_from_oracle(oracle)
+    fwd, dx, dw = run_fwd_bwd(spo, case, one_call=one_call)
+    ref = check_forward(case, oracle, fwd)
+    rb = oracle.pg_loss_bwd(*case.oracle_inputs(), *case.eps)
+    n_active = int(np.count_nonzero(rb["g"]))
+    rows = T if (one_call and mask_frac is None) else n_active
+    assert 8192 < rows <= 8448, rows        # 33 row tiles: a last round of 8 tiles
+    got = f64(dx)
+    assert rel_l2(got, rb["d_hidden"]) < GRAD_TOL and rel_l2(f64(dw), rb["d_W"]) < GRAD_TOL
+    per_row = np.linalg.norm(got - rb["d_hidden"], axis=1)
+    scale = np.linalg.norm(rb["d_hidden"], axis=1)
+    assert (per_row <= 2 * GRAD_TOL * scale + 1e-12).all()     # every token's row, those of the cut tiles included
+    assert not got[scale == 0].any()
+
+
 DEEP = wl.scaled(wl.CONFIGS["C2"], name="deep", H=320, V=1100)
 DEEP_LENGTHS = [9000, 7000, 12001, 5000, 6999]  # T = 40000: 157 token tiles, three chunks of 16384
 
