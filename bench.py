@@ -251,7 +251,7 @@ def main() -> int:
         "config": {"workload": res["workload"], "T": T, "B": B, "H": H, "V": V, "N": cfg.N,
                    "eps": [cfg.eps_low, cfg.eps_high], "d_half": cfg.d_half,
                    "path": res["path"],
-                   "chunk_tokens": args.chunk_tokens or "library default (a piece's stored logits and logit gradients <= 8 GiB)",
+                   "chunk_tokens": args.chunk_tokens or "library default (what is stored of a piece, or the logit gradients of a chunk, <= 8 GiB)",
                    "workspace_bytes": res["workspace_bytes"]},
         "active_tokens": res["active_tokens"], "tflops_useful": res["tflops_useful"],
         "tflops_executed": res["tflops_executed"], "mfma_util_executed": res["mfma_util_executed"],
