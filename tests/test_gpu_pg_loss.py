@@ -116,6 +116,32 @@ def test_backward_chunks_and_output_dtypes(spo, oracle, one_call):
     assert rel_l2(f64(dx3), rb["d_hidden"]) < GRAD_TOL and rel_l2(f64(dw3), rb["d_W"]) < GRAD_TOL
 
 
+@pytest.mark.parametrize("mask_frac", [None, 0.25], ids=["no_mask", "masked"])
+def test_one_call_with_only_one_of_the_two_gradients(spo, oracle, mask_frac):
+    # d_hidden alone, d_W alone, neither (loss and log-probs only): the one call skips what is not asked for
+    say(f"one call, single outputs, mask={mask_frac}")
+    case = Case(MID, MID_LENGTHS, mask_frac=mask_frac)
+    case.set_old_from_oracle(oracle)
+    desc = case.to_gpu(spo)
+    rb = oracle.pg_loss_bwd(*case.oracle_inputs(), *case.eps)
+    *fwd, dx, dw = spo.spo_pg_loss_fwd_bwd(desc, 1.0, d_hidden_dtype=torch.float32, want_d_W=False)
+    torch.cuda.synchronize()
+    check_forward(case, oracle, tuple(fwd))
+    assert dw is None and rel_l2(f64(dx), rb["d_hidden"]) < GRAD_TOL
+    *fwd, dx, dw = spo.spo_pg_loss_fwd_bwd(desc, 1.0, want_d_hidden=False)
+    torch.cuda.synchronize()
+    check_forward(case, oracle, tuple(fwd))
+    assert dx is None and rel_l2(f64(dw), rb["d_W"]) < GRAD_TOL
+    *fwd, dx, dw = spo.spo_pg_loss_fwd_bwd(desc, 1.0, want_d_hidden=False, want_d_W=False)
+    torch.cuda.synchronize()
+    check_forward(case, oracle, tuple(fwd))
+    assert dx is None and dw is None
+    # grad_loss scales both gradients
+    _, _, _, _, dx2, dw2 = spo.spo_pg_loss_fwd_bwd(desc, -2.5, d_hidden_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert rel_l2(f64(dx2), -2.5 * rb["d_hidden"]) < GRAD_TOL and rel_l2(f64(dw2), -2.5 * rb["d_W"]) < GRAD_TOL
+
+
 @pytest.mark.parametrize("w_layout", [0, 1])
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
 def test_head_gradient_on_ragged_shapes(spo, oracle, w_layout, dtype, one_call):
