@@ -338,8 +338,8 @@ int spo_pg_loss_fwd_bwd(const spo_pg_desc *d, float grad_loss, float *loss, floa
                         void *ws, size_t ws_bytes, spo_stream_t stream);
 
 /* ---------------------------------------------------------------------------
- * Per-kernel timing (measurement aid, not part of the method; the only state
- * the library keeps).  While enabled, the loss entry points bracket each launch
+ * Per-kernel timing (measurement aid, not part of the method; with the static
+ * buffer of spo_sample_prompts_static the only state the library keeps).  While enabled, the loss entry points bracket each launch
  * of their heavy kernels with a pair of HIP events on the launch stream.
  * spo_kernel_timing_read waits for the recorded events, writes the summed
  * milliseconds and the number of launches per kernel class, and forgets them.
